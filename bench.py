@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the CGBN hot path on one MI355X.
+
+A step is one pass of the whole path -- cgbn_forward then cgbn_backward -- over
+one synthetic activation tensor that is already resident in HBM.  The headline
+workload is the detector stem level (16 x 64 x 400 x 672, NCHW fp32, K = 8
+shards).  `value` is the effective bandwidth: the algorithmic byte count of the
+two-pass method (9 sweeps of the tensor: 3 reads + 1 write forward, 4 reads +
+1 write backward) divided by the step time.  Fewer bytes may really move (a
+sweep can start on what the previous one left in cache); the measured traffic
+is reported beside it.
+
+Prints ONE JSON line.  `roofline` is for the dominant kernel (the dx sweep),
+timed on its own with HIP events on the stream it is launched on;
+`cpu_baseline` is the float64 oracle timed on this machine's host cores on a
+sample of channels of the same workload.
+"""
+
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_GBPS = 8000.0   # MI355X HBM3E, published
+METRIC = "CGBN fwd+bwd ms/layer and effective HBM GB/s (% of MI355X peak), 1 GPU"
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Layer:
+    """Device buffers of one CGBN layer plus the calls that make up a step."""
+
+    def __init__(self, wl, torch, cgbn, x, dy, gamma, beta):
+        self.wl, self.cgbn, self.torch = wl, cgbn, torch
+        dev = x.device
+        self.x, self.dy, self.gamma, self.beta = x, dy, gamma, beta
+        self.y, self.dx = torch.empty_like(x), torch.empty_like(x)
+        v = lambda: torch.empty(wl.C, dtype=torch.float32, device=dev)
+        self.mean, self.invstd, self.mean_lo, self.dgamma, self.dbeta = v(), v(), v(), v(), v()
+        wb = cgbn.cgbn_workspace_bytes(wl.N, wl.C, wl.H, wl.W, wl.layout, wl.dtype, wl.K)
+        self.ws = torch.empty(wb, dtype=torch.uint8, device=dev)
+        f64 = lambda: torch.empty(wl.K * wl.C, dtype=torch.float64, device=dev)
+        self.s, self.v, self.a, self.b = f64(), f64(), f64(), f64()
+        self.shape = (wl.N, wl.C, wl.H, wl.W)
+
+    def forward(self):
+        wl = self.wl
+        self.cgbn.cgbn_forward(self.x, *self.shape, wl.layout, wl.K, self.gamma, self.beta, wl.eps,
+                               self.y, self.mean, self.invstd, wl.dtype, self.mean_lo, self.ws)
+
+    def backward(self):
+        wl = self.wl
+        self.cgbn.cgbn_backward(self.dy, self.x, self.mean, self.invstd, self.gamma, self.dx,
+                                self.dgamma, self.dbeta, *self.shape, wl.layout, wl.K, wl.dtype,
+                                self.mean_lo, self.ws)
+
+    def step(self):
+        self.forward()
+        self.backward()
+
+    # the sweeps one at a time (same kernels as the fused entry points)
+    def sweeps(self):
+        wl, c, sh = self.wl, self.cgbn, self.shape
+        M = wl.M
+        return {
+            "shard_sum": (1, lambda: c.cgbn_shard_sum(self.x, *sh, wl.layout, wl.K, wl.dtype, self.s, self.ws)),
+            "shard_sqdev": (1, lambda: c.cgbn_shard_sqdev(self.x, *sh, wl.layout, wl.K, wl.dtype, self.mean,
+                                                          self.mean_lo, self.v, self.ws)),
+            "normalize": (2, lambda: c.cgbn_normalize(self.x, *sh, wl.layout, wl.dtype, self.mean, self.mean_lo,
+                                                      self.invstd, self.gamma, self.beta, self.y)),
+            "backward_shard_sums": (2, lambda: c.cgbn_backward_shard_sums(
+                self.dy, self.x, *sh, wl.layout, wl.K, wl.dtype, self.mean, self.mean_lo, self.invstd,
+                self.a, self.b, self.ws)),
+            "backward_dx": (3, lambda: c.cgbn_backward_dx(self.dy, self.x, *sh, wl.layout, wl.dtype, self.mean,
+                                                          self.mean_lo, self.invstd, self.gamma, self.dgamma,
+                                                          self.dbeta, self.dx)),
+        }
+
+
+def device_inputs_host_recipe(wl, torch, synth, dev):
+    d = synth.make_inputs(wl, threads=min(16, os.cpu_count() or 1))
+    conv = lambda a: torch.from_numpy(a.view("int16") if a.dtype.name == "uint16" else a).to(dev)
+    return conv(d["x"]), conv(d["dy"]), torch.from_numpy(d["gamma"]).to(dev), torch.from_numpy(d["beta"]).to(dev)
+
+
+def device_inputs_fast(wl, torch, synth, dev):
+    """Same distributions drawn on the device (used for the secondary workloads,
+    where only timing is taken)."""
+    mu, sigma, gamma, beta = (torch.from_numpy(a).to(dev) for a in synth.channel_params(wl))
+    g = torch.Generator(device=dev)
+    g.manual_seed(wl.seed)
+    shape = (wl.N, wl.C, wl.H, wl.W) if wl.layout == "NCHW" else (wl.N, wl.H, wl.W, wl.C)
+    bs = (1, -1, 1, 1) if wl.layout == "NCHW" else (1, 1, 1, -1)
+    x = torch.randn(shape, generator=g, device=dev, dtype=torch.float32)
+    x.mul_(sigma.view(bs)).add_(mu.view(bs))
+    if wl.x_kind == "relu":
+        x.clamp_(min=0)
+    dy = torch.randn(shape, generator=g, device=dev, dtype=torch.float32).mul_(wl.dy_sigma)
+    if wl.dtype == "bf16":
+        x, dy = x.to(torch.bfloat16).view(torch.int16), dy.to(torch.bfloat16).view(torch.int16)
+    return x, dy, gamma, beta
+
+
+def time_calls(torch, fn, warmup, iters):
+    """Per-call durations in ms from HIP events on the current stream."""
+    for _ in range(warmup):
+        fn()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    torch.cuda.synchronize()
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return [a.elapsed_time(b) for a, b in ev]
+
+
+def measure_workload(layer, torch, steps, warmup):
+    wl = layer.wl
+    Sb = wl.S * wl.elem_bytes
+    for _ in range(warmup):
+        layer.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        layer.step()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    fwd = statistics.median(time_calls(torch, layer.forward, 2, max(5, steps // 2)))
+    bwd = statistics.median(time_calls(torch, layer.backward, 2, max(5, steps // 2)))
+    return dict(
+        workload=wl.name, ms_per_step=wall_ms, fwd_ms=fwd, bwd_ms=bwd,
+        effective_GBps=9 * Sb / wall_ms / 1e6, pct_of_peak=9 * Sb / wall_ms / 1e6 / PEAK_GBPS * 100,
+        floor_GBps=5 * Sb / wall_ms / 1e6,
+        fwd_effective_GBps=4 * Sb / fwd / 1e6, bwd_effective_GBps=5 * Sb / bwd / 1e6)
+
+
+def cpu_baseline(wl, synth, budget_s=12.0):
+    """The float64 oracle (plain definition, forward + backward) on host cores,
+    on channels of the same workload, sized to about `budget_s` seconds."""
+    from oracle import cgbn_oracle as O
+    workers = max(1, min(16, os.cpu_count() or 1))
+    per = wl.M * wl.elem_bytes * 9
+
+    def draw(c):
+        d = synth.make_inputs(wl, channels=[c], threads=1)
+        if wl.dtype == "bf16":
+            d["x"], d["dy"] = O.bf16_bits_to_f64(d["x"]), O.bf16_bits_to_f64(d["dy"])
+        return d
+
+    def run(d):
+        O.cgbn_forward_backward_ref(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout)
+
+    d0 = draw(0)
+    t = time.perf_counter()
+    run(d0)                                             # one channel alone: sizes the sample
+    t_one = time.perf_counter() - t
+    rounds = max(1, min(wl.C // workers, int(budget_s / max(t_one, 1e-3))))
+    chans = list(range(workers * rounds))
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        inputs = list(ex.map(draw, chans))              # untimed
+        t = time.perf_counter()
+        list(ex.map(run, inputs))
+        wall = time.perf_counter() - t
+    return dict(value=per * len(chans) / wall / 1e9, unit="GB/s", cores=workers, kind="oracle",
+                sample=f"{len(chans)} of {wl.C} channels of {wl.name}, forward+backward, float64 numpy, "
+                       f"{workers} threads with one channel each, {wall:.2f} s wall",
+                ms_per_layer_extrapolated=wall / len(chans) * wl.C * 1e3)
+
+
+def load_traffic(name):
+    """Measured HBM bytes per launch of the dominant kernel, from the committed
+    rocprofv3 counter summary (profiles/traffic.json), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(name)
+    except (OSError, ValueError):
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="cfg1")
+    ap.add_argument("--others", default="cfg2,cfg3,cfg4", help="secondary workloads timed with fewer steps ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (the K shards are virtual devices on it); "
+                 "--gpus N with N > 1 is not supported")
+
+    import torch
+    from paper_1711_07240_amd import cgbn, synth
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    cgbn.lib()                       # fail loudly if the HIP library is not built
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    wl = synth.WORKLOADS[args.workload]
+    log(f"[bench] drawing {wl.name} on the host ({wl.S} elements x 2)")
+    x, dy, gamma, beta = device_inputs_host_recipe(wl, torch, synth, dev)
+    layer = Layer(wl, torch, cgbn, x, dy, gamma, beta)
+    log("[bench] timing the step")
+    head = measure_workload(layer, torch, args.steps, args.warmup)
+
+    # dominant kernel on its own: the dx sweep (reads dy and x, writes dx)
+    Sb = wl.S * wl.elem_bytes
+    sweeps = {}
+    for name, (ntensors, fn) in layer.sweeps().items():
+        ms = time_calls(torch, fn, 3, max(10, args.steps // 2))
+        sweeps[name] = dict(ms=statistics.mean(ms), GBps=ntensors * Sb / statistics.mean(ms) / 1e6)
+    dom = "backward_dx"
+    roofline = dict(bound="hbm", kernel=dom, achieved=sweeps[dom]["GBps"], peak=PEAK_GBPS, unit="GB/s",
+                    frac=sweeps[dom]["GBps"] / PEAK_GBPS, traffic=load_traffic(f"{wl.name}.{dom}"),
+                    avg_ms=sweeps[dom]["ms"], algorithmic_bytes=3 * Sb)
+
+    others = []
+    del layer, x, dy
+    torch.cuda.empty_cache()
+    for name in [n for n in args.others.split(",") if n and n != wl.name]:
+        w2 = synth.WORKLOADS[name]
+        log(f"[bench] secondary workload {name}")
+        l2 = Layer(w2, torch, cgbn, *device_inputs_fast(w2, torch, synth, dev))
+        others.append(measure_workload(l2, torch, max(5, args.steps // 5), max(2, args.warmup // 2)))
+        del l2
+        torch.cuda.empty_cache()
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        log("[bench] timing the float64 oracle on the host")
+        cpu = cpu_baseline(wl, synth)
+
+    out = {
+        "metric": METRIC, "value": head["effective_GBps"], "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if wl.dtype == "f32" else "bf16 storage, f32 arithmetic",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.name}: N={wl.N} C={wl.C} H={wl.H} W={wl.W} {wl.layout} {wl.dtype} K={wl.K}",
+                   "step": "cgbn_forward + cgbn_backward", "algorithmic_bytes": 9 * Sb,
+                   "tuning": {k: cgbn.cgbn_get_tuning(k) for k in
+                              ("chunk_bytes", "wave_plane_bytes", "piece_bytes", "reverse", "nt_store")}},
+        "pct_of_peak": head["pct_of_peak"], "fwd_ms": head["fwd_ms"], "bwd_ms": head["bwd_ms"],
+        "floor_GBps": head["floor_GBps"],
+        "sweeps": sweeps, "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,
+        "device": torch.cuda.get_device_name(0),
+    }
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,155 @@
+/*
+ * libcgbn -- Cross-GPU Batch Normalization (CGBN) forward and backward for one
+ * MI355X (gfx950), with the method's n devices appearing as K "virtual
+ * devices": K contiguous, equal sub-batch shards of one activation tensor.
+ *
+ * Method: MegDet, section 3.3 "Cross-GPU Batch Normalization", Algorithm 1.
+ *   steps 1-3   device sums            s[k,c] = sum over shard k of x
+ *   steps 4-5   reduce + broadcast     mean[c] = (sum_k s[k,c]) / M
+ *   steps 6-8   device variance sums   v[k,c] = sum over shard k of (x - mean[c])^2
+ *   steps 9-10  reduce + broadcast     var[c]  = (sum_k v[k,c]) / M   (biased)
+ *   step 11     y = gamma (x - mean)/sqrt(var + eps) + beta
+ * with M = N*H*W the pooled count per channel.  The paper gives no backward;
+ * the one here is the chain rule through the pooled mean and variance:
+ *   a[k,c] = sum over shard k of dy,   b[k,c] = sum over shard k of dy*xhat
+ *   dbeta = sum_k a,  dgamma = sum_k b,  xhat = (x - mean) * invstd
+ *   dx = gamma * invstd * (dy - dbeta/M - xhat * dgamma/M)
+ *
+ * Conventions common to every entry point
+ *   - Every tensor/vector pointer is a DEVICE pointer owned by the caller; the
+ *     library never allocates, frees or keeps device memory.  Scratch is the
+ *     caller's `workspace` (size from cgbn_workspace_bytes, contents undefined
+ *     after a call).  Activation tensors (x, y, dy, dx) are dense in `layout`
+ *     with element type `dtype`, their base address 16-byte aligned.  Per-channel
+ *     vectors are float[C]; shard partials are double[K*C], index k*C + c.
+ *   - Shard k holds images [k*N/K, (k+1)*N/K); 1 <= K <= N and N % K == 0.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream).  No call synchronises or reads back.
+ *   - Errors: the return code only.  Argument errors are found on the host
+ *     before any launch and leave every output untouched.  CGBN_ERR_HIP wraps a
+ *     failed launch.  NaN/Inf in the data are not errors; they propagate within
+ *     their channel.
+ *   - Aliasing: y may be exactly x, dx may be exactly dy; any other overlap of
+ *     an output with another argument is undefined.
+ *   - `mean_lo` (optional, may be NULL everywhere): float[C] holding the part of
+ *     the pooled mean that does not fit `mean`'s float, mean + mean_lo being the
+ *     mean to about double precision.  The forward uses it internally in any
+ *     case; exporting it lets the backward see the same mean when |mean| is
+ *     orders of magnitude above the channel's spread.
+ *   - Results are bitwise reproducible run to run (fixed summation order, no
+ *     floating-point atomics) and depend on K only through rounding.
+ */
+#ifndef CGBN_H
+#define CGBN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum cgbn_status {
+    CGBN_OK = 0,
+    CGBN_ERR_NULL = 1,       /* a required pointer is NULL */
+    CGBN_ERR_SHAPE = 2,      /* a dimension is < 1 or the tensor is too large to index */
+    CGBN_ERR_SHARD = 3,      /* K < 1, K > N or N % K != 0 */
+    CGBN_ERR_ENUM = 4,       /* layout or dtype out of range */
+    CGBN_ERR_EPS = 5,        /* eps is not finite and > 0 */
+    CGBN_ERR_WORKSPACE = 6,  /* workspace NULL, misaligned (256 B) or too small */
+    CGBN_ERR_ALIGN = 7,      /* an activation tensor is not 16-byte aligned */
+    CGBN_ERR_HIP = 8,        /* the HIP runtime refused a launch */
+    CGBN_ERR_TUNING = 9      /* unknown tuning key or value out of range */
+} cgbn_status;
+
+typedef enum cgbn_layout { CGBN_NCHW = 0, CGBN_NHWC = 1 } cgbn_layout;
+typedef enum cgbn_dtype { CGBN_F32 = 0, CGBN_BF16 = 1 } cgbn_dtype; /* of x, y, dy, dx */
+
+/* Bytes of workspace any entry point below needs for this problem (a multiple
+ * of 256; the workspace itself must be 256-byte aligned).  Returns 0 if the
+ * arguments are invalid.  Host-only, launches nothing. */
+size_t cgbn_workspace_bytes(int N, int C, int H, int W, cgbn_layout layout,
+                            cgbn_dtype dtype, int K);
+
+/* Algorithm 1, all steps.  In: x, gamma[C], beta[C], eps.  Out: y (same shape,
+ * layout and dtype as x; bf16 rounded to nearest-even), mean[C], invstd[C] =
+ * 1/sqrt(var + eps), and mean_lo[C] if not NULL. */
+cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                         const float* gamma, const float* beta, float eps,
+                         void* y, float* mean, float* invstd,
+                         cgbn_dtype dtype, float* mean_lo,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward of Algorithm 1's last step through the pooled statistics.  In: dy, x,
+ * mean[C], invstd[C] as written by cgbn_forward, gamma[C], mean_lo[C] or NULL.
+ * Out: dx, dgamma[C], dbeta[C]. */
+cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, const float* invstd,
+                          const float* gamma, void* dx, float* dgamma, float* dbeta,
+                          int N, int C, int H, int W, cgbn_layout layout, int K,
+                          cgbn_dtype dtype, const float* mean_lo,
+                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* ---- The same path one step at a time (cgbn_forward and cgbn_backward run
+ * exactly these kernels back to back).  Meant for tests and measurement. ---- */
+
+/* Algorithm 1 steps 1-3: s[k*C + c] = sum over shard k of x. */
+cgbn_status cgbn_shard_sum(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                           cgbn_dtype dtype, double* s,
+                           void* workspace, size_t workspace_bytes, void* stream);
+
+/* Steps 4-5: mean[c] = (sum_k s[k,c]) / M, with M given as a count.  mean_lo optional. */
+cgbn_status cgbn_reduce_mean(const double* s, int K, int C, long long M,
+                             float* mean, float* mean_lo, void* stream);
+
+/* Steps 6-8: v[k*C + c] = sum over shard k of (x - mean[c])^2 (mean_lo optional). */
+cgbn_status cgbn_shard_sqdev(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                             cgbn_dtype dtype, const float* mean, const float* mean_lo, double* v,
+                             void* workspace, size_t workspace_bytes, void* stream);
+
+/* Steps 9-10: invstd[c] = 1/sqrt((sum_k v[k,c])/M + eps). */
+cgbn_status cgbn_reduce_invstd(const double* v, int K, int C, long long M, float eps,
+                               float* invstd, void* stream);
+
+/* Step 11: y = gamma*(x - mean)*invstd + beta. */
+cgbn_status cgbn_normalize(const void* x, int N, int C, int H, int W, cgbn_layout layout,
+                           cgbn_dtype dtype, const float* mean, const float* mean_lo,
+                           const float* invstd, const float* gamma, const float* beta,
+                           void* y, void* stream);
+
+/* Backward device sums: a[k*C + c] = sum dy, b[k*C + c] = sum dy*xhat over shard k. */
+cgbn_status cgbn_backward_shard_sums(const void* dy, const void* x, int N, int C, int H, int W,
+                                     cgbn_layout layout, int K, cgbn_dtype dtype,
+                                     const float* mean, const float* mean_lo, const float* invstd,
+                                     double* a, double* b,
+                                     void* workspace, size_t workspace_bytes, void* stream);
+
+/* Backward reduce: dbeta[c] = sum_k a[k,c], dgamma[c] = sum_k b[k,c]. */
+cgbn_status cgbn_backward_reduce(const double* a, const double* b, int K, int C,
+                                 float* dbeta, float* dgamma, void* stream);
+
+/* dx = gamma*invstd*(dy - dbeta/M - xhat*dgamma/M). */
+cgbn_status cgbn_backward_dx(const void* dy, const void* x, int N, int C, int H, int W,
+                             cgbn_layout layout, cgbn_dtype dtype,
+                             const float* mean, const float* mean_lo, const float* invstd,
+                             const float* gamma, const float* dgamma, const float* dbeta,
+                             void* dx, void* stream);
+
+/* ---- housekeeping ---- */
+
+/* Static, never NULL. */
+const char* cgbn_status_string(cgbn_status status);
+
+/* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe;
+ * change them only between calls and re-query cgbn_workspace_bytes afterwards).
+ *   "chunk_bytes"      NCHW: bytes of one plane handled by one workgroup
+ *   "wave_plane_bytes" NCHW: planes up to this size are handled by one wavefront
+ *   "piece_bytes"      NHWC: bytes of one pixel range handled by one workgroup
+ *   "reverse"          0/1: alternate the sweep direction between consecutive sweeps
+ *   "nt_store"         0/1: non-temporal stores for y and dx
+ * cgbn_get_tuning returns -1 for an unknown key. */
+cgbn_status cgbn_set_tuning(const char* key, long long value);
+long long cgbn_get_tuning(const char* key);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CGBN_H */

@@ -1,0 +1,462 @@
+// Host side of libcgbn: argument validation, launch plan, launches, C ABI.
+// See include/cgbn.h for the contract of every entry point.
+
+#include "cgbn.h"
+#include "cgbn_kernels.h"
+
+#include <cmath>
+#include <cstring>
+
+namespace {
+
+using namespace cgbn;
+
+// ---- launch-shape knobs (cgbn_set_tuning) ---------------------------------
+struct Tuning {
+    long long chunk_bytes = 32768;       // NCHW: bytes of a plane per workgroup
+    long long wave_plane_bytes = 16384;  // NCHW: planes up to this go one per wavefront
+    long long piece_bytes = 131072;      // NHWC: bytes of a pixel run per workgroup (full channel width)
+    long long reverse = 1;               // alternate sweep direction so a sweep starts on what the last one left in cache
+    long long nt_store = 1;              // non-temporal stores for y and dx
+};
+Tuning g_tune;
+
+struct Plan {
+    int N, C, H, W, K, layout, dtype;
+    int eb, vec;          // bytes per element; elements per 16-byte vector (NHWC: 1 if C is not a multiple)
+    int HW, ips;
+    long long S;
+    double M;
+    // NCHW
+    int wave_mode, L, sp;
+    // NHWC
+    int cv, TW, ctiles, rpp, PL, pps;
+    long long spix;
+    // partial sums
+    int rows, rps, G;
+    long long grid;       // workgroups of one sweep
+    // workspace layout (byte offsets)
+    size_t off_part0, off_part1, off_sh0, off_sh1, off_mlo, bytes;
+};
+
+size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, Plan* p)
+{
+    if (N < 1 || C < 1 || H < 1 || W < 1) return CGBN_ERR_SHAPE;
+    if (layout != CGBN_NCHW && layout != CGBN_NHWC) return CGBN_ERR_ENUM;
+    if (dtype != CGBN_F32 && dtype != CGBN_BF16) return CGBN_ERR_ENUM;
+    if (K < 1 || K > N || N % K != 0) return CGBN_ERR_SHARD;
+    long long HW = (long long)H * W;
+    if (HW > 0x3fffffffLL) return CGBN_ERR_SHAPE;
+    long long planes = (long long)N * C;
+    if (planes > 0x3fffffffLL) return CGBN_ERR_SHAPE;
+    long long S = planes * HW;
+    if (S > (1LL << 40)) return CGBN_ERR_SHAPE;
+    std::memset(p, 0, sizeof(*p));
+    p->N = N; p->C = C; p->H = H; p->W = W; p->K = K; p->layout = layout; p->dtype = dtype;
+    p->eb = dtype == CGBN_F32 ? 4 : 2;
+    p->HW = (int)HW;
+    p->ips = N / K;
+    p->S = S;
+    p->M = (double)N * (double)HW;
+    const int full_vec = 16 / p->eb;
+    if (layout == CGBN_NCHW) {
+        p->vec = full_vec;
+        if (HW * p->eb <= g_tune.wave_plane_bytes) {
+            p->wave_mode = 1;
+            p->L = (int)HW;
+            p->sp = 1;
+            p->grid = (planes + 3) / 4;
+        } else {
+            long long L = g_tune.chunk_bytes / p->eb;
+            L -= L % (kThreads * full_vec);                    // whole vectors for every thread
+            if (L < kThreads * full_vec) L = kThreads * full_vec;
+            if (L > HW) L = HW;
+            p->L = (int)L;
+            p->sp = (int)((HW + L - 1) / L);
+            p->grid = planes * p->sp;
+        }
+        p->rows = N * p->sp;
+        p->rps = p->ips * p->sp;
+    } else {
+        p->vec = (C % full_vec == 0) ? full_vec : 1;
+        p->cv = C / p->vec;
+        p->TW = p->cv < kThreads ? p->cv : kThreads;
+        p->ctiles = (p->cv + p->TW - 1) / p->TW;
+        p->rpp = kThreads / p->TW;
+        p->spix = (long long)p->ips * HW;
+        long long PL = g_tune.piece_bytes / ((long long)C * p->eb);
+        PL -= PL % (4 * p->rpp);                               // four pixels per thread and pass
+        if (PL < 4 * p->rpp) PL = 4 * p->rpp;
+        if (PL > p->spix) PL = p->spix;
+        p->PL = (int)PL;
+        long long pps = (p->spix + PL - 1) / PL;
+        if (pps * K > 0x3fffffffLL) return CGBN_ERR_SHAPE;
+        p->pps = (int)pps;
+        p->rows = (int)(pps * K);
+        p->rps = (int)pps;
+        p->grid = (long long)p->rows * p->ctiles;
+    }
+    if (p->grid > 0x7fffffffLL || (long long)p->rows * C > (1LL << 33)) return CGBN_ERR_SHAPE;
+    int G = 1;
+    while (G < kWave && G < p->rps) G <<= 1;
+    p->G = G;
+    size_t part = align256((size_t)C * p->rows * sizeof(float));
+    size_t sh = align256((size_t)K * C * sizeof(double));
+    p->off_part0 = 0;
+    p->off_part1 = part;
+    p->off_sh0 = 2 * part;
+    p->off_sh1 = 2 * part + sh;
+    p->off_mlo = 2 * part + 2 * sh;
+    p->bytes = p->off_mlo + align256((size_t)C * sizeof(float));
+    return CGBN_OK;
+}
+
+bool aligned16(const void* p) { return ((uintptr_t)p & 15u) == 0; }
+
+cgbn_status check_ws(const Plan& p, const void* ws, size_t bytes)
+{
+    if (!ws || ((uintptr_t)ws & 255u) != 0 || bytes < p.bytes) return CGBN_ERR_WORKSPACE;
+    return CGBN_OK;
+}
+
+cgbn_status launched()
+{
+    return hipGetLastError() == hipSuccess ? CGBN_OK : CGBN_ERR_HIP;
+}
+
+SweepArgs sweep_args(const Plan& p)
+{
+    SweepArgs A;
+    std::memset(&A, 0, sizeof(A));
+    A.S = p.S; A.N = p.N; A.C = p.C; A.HW = p.HW; A.rows = p.rows;
+    A.L = p.L; A.sp = p.sp;
+    A.cv = p.cv; A.TW = p.TW; A.ctiles = p.ctiles; A.rpp = p.rpp; A.PL = p.PL; A.pps = p.pps;
+    A.spix = p.spix;
+    A.pivot_stride = p.layout == CGBN_NCHW ? p.HW : 1;
+    A.inv_M = (float)(1.0 / p.M);
+    A.nt = (int)g_tune.nt_store;
+    return A;
+}
+
+template <typename T, int OP> void launch_reduce_t(const Plan& p, const SweepArgs& A, hipStream_t st)
+{
+    dim3 grid((unsigned)p.grid), block(kThreads);
+    if (p.layout == CGBN_NCHW) {
+        if (p.wave_mode) hipLaunchKernelGGL((nchw_reduce_wave<T, OP>), grid, block, 0, st, A);
+        else hipLaunchKernelGGL((nchw_reduce_block<T, OP>), grid, block, 0, st, A);
+    } else {
+        if (p.vec == 1) hipLaunchKernelGGL((nhwc_reduce<T, 1, OP>), grid, block, 0, st, A);
+        else hipLaunchKernelGGL((nhwc_reduce<T, Elem<T>::VEC, OP>), grid, block, 0, st, A);
+    }
+}
+
+template <typename T, int EL> void launch_map_t(const Plan& p, const SweepArgs& A, hipStream_t st)
+{
+    dim3 grid((unsigned)p.grid), block(kThreads);
+    if (p.layout == CGBN_NCHW) {
+        if (p.wave_mode) hipLaunchKernelGGL((nchw_map_wave<T, EL>), grid, block, 0, st, A);
+        else hipLaunchKernelGGL((nchw_map_block<T, EL>), grid, block, 0, st, A);
+    } else {
+        if (p.vec == 1) hipLaunchKernelGGL((nhwc_map<T, 1, EL>), grid, block, 0, st, A);
+        else hipLaunchKernelGGL((nhwc_map<T, Elem<T>::VEC, EL>), grid, block, 0, st, A);
+    }
+}
+
+cgbn_status launch_reduce(int op, const Plan& p, const SweepArgs& A, hipStream_t st)
+{
+    const bool f32 = p.dtype == CGBN_F32;
+    switch (op) {
+    case OP_SUM:   f32 ? launch_reduce_t<float, OP_SUM>(p, A, st)   : launch_reduce_t<bf16_t, OP_SUM>(p, A, st); break;
+    case OP_SQDEV: f32 ? launch_reduce_t<float, OP_SQDEV>(p, A, st) : launch_reduce_t<bf16_t, OP_SQDEV>(p, A, st); break;
+    default:       f32 ? launch_reduce_t<float, OP_BWD>(p, A, st)   : launch_reduce_t<bf16_t, OP_BWD>(p, A, st); break;
+    }
+    return launched();
+}
+
+cgbn_status launch_map(int el, const Plan& p, const SweepArgs& A, hipStream_t st)
+{
+    const bool f32 = p.dtype == CGBN_F32;
+    if (el == EL_NORM) f32 ? launch_map_t<float, EL_NORM>(p, A, st) : launch_map_t<bf16_t, EL_NORM>(p, A, st);
+    else               f32 ? launch_map_t<float, EL_DX>(p, A, st)   : launch_map_t<bf16_t, EL_DX>(p, A, st);
+    return launched();
+}
+
+// `pivot_x`: the activation tensor when the rows hold sums about the channel pivots
+// (the plain-sum sweep), else null.
+cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float* out1, float* out2,
+                           double* sh0, double* sh1, double eps, const void* pivot_x, hipStream_t st)
+{
+    CombineArgs A;
+    std::memset(&A, 0, sizeof(A));
+    A.part0 = reinterpret_cast<const float*>(ws + p.off_part0);
+    A.part1 = reinterpret_cast<const float*>(ws + p.off_part1);
+    A.sh0 = sh0; A.sh1 = sh1;
+    A.out0 = out0; A.out1 = out1; A.out2 = out2;
+    A.M = p.M; A.eps = eps;
+    A.shard_count = p.M / p.K;
+    A.x = pivot_x;
+    A.pivot_stride = pivot_x ? (p.layout == CGBN_NCHW ? p.HW : 1) : 0;
+    A.is_bf16 = p.dtype == CGBN_BF16;
+    A.C = p.C; A.rows = p.rows; A.K = p.K; A.rps = p.rps; A.G = p.G;
+    dim3 grid((unsigned)((p.C + 3) / 4)), block(kThreads);
+    switch (mode) {
+    case CM_MEAN:   hipLaunchKernelGGL((combine_rows<CM_MEAN>), grid, block, 0, st, A); break;
+    case CM_INVSTD: hipLaunchKernelGGL((combine_rows<CM_INVSTD>), grid, block, 0, st, A); break;
+    case CM_BWD:    hipLaunchKernelGGL((combine_rows<CM_BWD>), grid, block, 0, st, A); break;
+    case CM_SHARDS2: hipLaunchKernelGGL((combine_rows<CM_SHARDS2>), grid, block, 0, st, A); break;
+    default:        hipLaunchKernelGGL((combine_rows<CM_SHARDS1>), grid, block, 0, st, A); break;
+    }
+    return launched();
+}
+
+bool eps_ok(float eps) { return std::isfinite(eps) && eps > 0.f; }
+
+#define CGBN_TRY(expr) do { cgbn_status s_ = (expr); if (s_ != CGBN_OK) return s_; } while (0)
+
+}  // namespace
+
+// ===========================================================================
+// C ABI
+// ===========================================================================
+
+extern "C" {
+
+size_t cgbn_workspace_bytes(int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype, int K)
+{
+    Plan p;
+    if (make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return 0;
+    return p.bytes;
+}
+
+cgbn_status cgbn_shard_sum(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                           cgbn_dtype dtype, double* s, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !s) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    if (!aligned16(x)) return CGBN_ERR_ALIGN;
+    CGBN_TRY(check_ws(p, workspace, workspace_bytes));
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SweepArgs A = sweep_args(p);
+    A.x = x;
+    A.part0 = reinterpret_cast<float*>(ws + p.off_part0);
+    CGBN_TRY(launch_reduce(OP_SUM, p, A, st));
+    return launch_combine(CM_SHARDS1, p, ws, nullptr, nullptr, nullptr, s, nullptr, 0.0, x, st);
+}
+
+cgbn_status cgbn_reduce_mean(const double* s, int K, int C, long long M, float* mean, float* mean_lo, void* stream)
+{
+    if (!s || !mean) return CGBN_ERR_NULL;
+    if (C < 1 || M < 1) return CGBN_ERR_SHAPE;
+    if (K < 1) return CGBN_ERR_SHARD;
+    dim3 grid((unsigned)((C + kThreads - 1) / kThreads)), block(kThreads);
+    hipLaunchKernelGGL((combine_shards<CM_MEAN>), grid, block, 0, static_cast<hipStream_t>(stream),
+                       s, (const double*)nullptr, K, C, (double)M, 0.0, mean, mean_lo);
+    return launched();
+}
+
+cgbn_status cgbn_shard_sqdev(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                             cgbn_dtype dtype, const float* mean, const float* mean_lo, double* v,
+                             void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !mean || !v) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    if (!aligned16(x)) return CGBN_ERR_ALIGN;
+    CGBN_TRY(check_ws(p, workspace, workspace_bytes));
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SweepArgs A = sweep_args(p);
+    A.x = x; A.mean = mean; A.mean_lo = mean_lo;
+    A.part0 = reinterpret_cast<float*>(ws + p.off_part0);
+    CGBN_TRY(launch_reduce(OP_SQDEV, p, A, st));
+    return launch_combine(CM_SHARDS1, p, ws, nullptr, nullptr, nullptr, v, nullptr, 0.0, nullptr, st);
+}
+
+cgbn_status cgbn_reduce_invstd(const double* v, int K, int C, long long M, float eps, float* invstd, void* stream)
+{
+    if (!v || !invstd) return CGBN_ERR_NULL;
+    if (C < 1 || M < 1) return CGBN_ERR_SHAPE;
+    if (K < 1) return CGBN_ERR_SHARD;
+    if (!eps_ok(eps)) return CGBN_ERR_EPS;
+    dim3 grid((unsigned)((C + kThreads - 1) / kThreads)), block(kThreads);
+    hipLaunchKernelGGL((combine_shards<CM_INVSTD>), grid, block, 0, static_cast<hipStream_t>(stream),
+                       v, (const double*)nullptr, K, C, (double)M, (double)eps, invstd, (float*)nullptr);
+    return launched();
+}
+
+cgbn_status cgbn_normalize(const void* x, int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype,
+                           const float* mean, const float* mean_lo, const float* invstd,
+                           const float* gamma, const float* beta, void* y, void* stream)
+{
+    if (!x || !mean || !invstd || !gamma || !beta || !y) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, 1, &p));
+    if (!aligned16(x) || !aligned16(y)) return CGBN_ERR_ALIGN;
+    SweepArgs A = sweep_args(p);
+    A.x = x; A.out = y; A.mean = mean; A.mean_lo = mean_lo; A.invstd = invstd; A.gamma = gamma; A.beta = beta;
+    return launch_map(EL_NORM, p, A, static_cast<hipStream_t>(stream));
+}
+
+cgbn_status cgbn_backward_shard_sums(const void* dy, const void* x, int N, int C, int H, int W,
+                                     cgbn_layout layout, int K, cgbn_dtype dtype,
+                                     const float* mean, const float* mean_lo, const float* invstd,
+                                     double* a, double* b, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!dy || !x || !mean || !invstd || !a || !b) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    if (!aligned16(x) || !aligned16(dy)) return CGBN_ERR_ALIGN;
+    CGBN_TRY(check_ws(p, workspace, workspace_bytes));
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    SweepArgs A = sweep_args(p);
+    A.x = x; A.dy = dy; A.mean = mean; A.mean_lo = mean_lo; A.invstd = invstd;
+    A.part0 = reinterpret_cast<float*>(ws + p.off_part0);
+    A.part1 = reinterpret_cast<float*>(ws + p.off_part1);
+    CGBN_TRY(launch_reduce(OP_BWD, p, A, st));
+    return launch_combine(CM_SHARDS2, p, ws, nullptr, nullptr, nullptr, a, b, 0.0, nullptr, st);
+}
+
+cgbn_status cgbn_backward_reduce(const double* a, const double* b, int K, int C,
+                                 float* dbeta, float* dgamma, void* stream)
+{
+    if (!a || !b || !dbeta || !dgamma) return CGBN_ERR_NULL;
+    if (C < 1) return CGBN_ERR_SHAPE;
+    if (K < 1) return CGBN_ERR_SHARD;
+    dim3 grid((unsigned)((C + kThreads - 1) / kThreads)), block(kThreads);
+    hipLaunchKernelGGL((combine_shards<CM_BWD>), grid, block, 0, static_cast<hipStream_t>(stream),
+                       a, b, K, C, 1.0, 0.0, dbeta, dgamma);
+    return launched();
+}
+
+cgbn_status cgbn_backward_dx(const void* dy, const void* x, int N, int C, int H, int W,
+                             cgbn_layout layout, cgbn_dtype dtype,
+                             const float* mean, const float* mean_lo, const float* invstd,
+                             const float* gamma, const float* dgamma, const float* dbeta,
+                             void* dx, void* stream)
+{
+    if (!dy || !x || !mean || !invstd || !gamma || !dgamma || !dbeta || !dx) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, 1, &p));
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx)) return CGBN_ERR_ALIGN;
+    SweepArgs A = sweep_args(p);
+    A.x = x; A.dy = dy; A.out = dx; A.mean = mean; A.mean_lo = mean_lo; A.invstd = invstd;
+    A.gamma = gamma; A.dgamma = dgamma; A.dbeta = dbeta;
+    return launch_map(EL_DX, p, A, static_cast<hipStream_t>(stream));
+}
+
+cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                         const float* gamma, const float* beta, float eps,
+                         void* y, float* mean, float* invstd,
+                         cgbn_dtype dtype, float* mean_lo,
+                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !gamma || !beta || !y || !mean || !invstd) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    if (!eps_ok(eps)) return CGBN_ERR_EPS;
+    if (!aligned16(x) || !aligned16(y)) return CGBN_ERR_ALIGN;
+    CGBN_TRY(check_ws(p, workspace, workspace_bytes));
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* part0 = reinterpret_cast<float*>(ws + p.off_part0);
+    double* sh0 = reinterpret_cast<double*>(ws + p.off_sh0);
+    float* mlo = reinterpret_cast<float*>(ws + p.off_mlo);
+    const int rev = (int)g_tune.reverse;
+
+    SweepArgs A = sweep_args(p);
+    A.x = x; A.part0 = part0;
+    // steps 1-3 then 4-5
+    CGBN_TRY(launch_reduce(OP_SUM, p, A, st));
+    CGBN_TRY(launch_combine(CM_MEAN, p, ws, mean, mlo, mean_lo, sh0, nullptr, 0.0, x, st));
+    // steps 6-8 then 9-10
+    A.mean = mean; A.mean_lo = mlo; A.reverse = rev;
+    CGBN_TRY(launch_reduce(OP_SQDEV, p, A, st));
+    CGBN_TRY(launch_combine(CM_INVSTD, p, ws, invstd, nullptr, nullptr, sh0, nullptr, (double)eps, nullptr, st));
+    // step 11
+    A.invstd = invstd; A.gamma = gamma; A.beta = beta; A.out = y; A.reverse = 0;
+    return launch_map(EL_NORM, p, A, st);
+}
+
+cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, const float* invstd,
+                          const float* gamma, void* dx, float* dgamma, float* dbeta,
+                          int N, int C, int H, int W, cgbn_layout layout, int K,
+                          cgbn_dtype dtype, const float* mean_lo,
+                          void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!dy || !x || !mean || !invstd || !gamma || !dx || !dgamma || !dbeta) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx)) return CGBN_ERR_ALIGN;
+    CGBN_TRY(check_ws(p, workspace, workspace_bytes));
+    char* ws = static_cast<char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int rev = (int)g_tune.reverse;
+
+    SweepArgs A = sweep_args(p);
+    A.x = x; A.dy = dy; A.mean = mean; A.mean_lo = mean_lo; A.invstd = invstd;
+    A.part0 = reinterpret_cast<float*>(ws + p.off_part0);
+    A.part1 = reinterpret_cast<float*>(ws + p.off_part1);
+    A.reverse = rev;
+    CGBN_TRY(launch_reduce(OP_BWD, p, A, st));
+    CGBN_TRY(launch_combine(CM_BWD, p, ws, dbeta, dgamma, nullptr,
+                            reinterpret_cast<double*>(ws + p.off_sh0), reinterpret_cast<double*>(ws + p.off_sh1),
+                            0.0, nullptr, st));
+    A.gamma = gamma; A.dgamma = dgamma; A.dbeta = dbeta; A.out = dx; A.reverse = 0;
+    return launch_map(EL_DX, p, A, st);
+}
+
+const char* cgbn_status_string(cgbn_status status)
+{
+    switch (status) {
+    case CGBN_OK: return "ok";
+    case CGBN_ERR_NULL: return "a required pointer is NULL";
+    case CGBN_ERR_SHAPE: return "a dimension is < 1 or the tensor is too large";
+    case CGBN_ERR_SHARD: return "need 1 <= K <= N and N % K == 0";
+    case CGBN_ERR_ENUM: return "layout or dtype out of range";
+    case CGBN_ERR_EPS: return "eps must be finite and > 0";
+    case CGBN_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned or too small";
+    case CGBN_ERR_ALIGN: return "activation tensors must be 16-byte aligned";
+    case CGBN_ERR_HIP: return "the HIP runtime refused a launch";
+    case CGBN_ERR_TUNING: return "unknown tuning key or value out of range";
+    }
+    return "unknown status";
+}
+
+static long long* tuning_slot(const char* key)
+{
+    if (!key) return nullptr;
+    if (!std::strcmp(key, "chunk_bytes")) return &g_tune.chunk_bytes;
+    if (!std::strcmp(key, "wave_plane_bytes")) return &g_tune.wave_plane_bytes;
+    if (!std::strcmp(key, "piece_bytes")) return &g_tune.piece_bytes;
+    if (!std::strcmp(key, "reverse")) return &g_tune.reverse;
+    if (!std::strcmp(key, "nt_store")) return &g_tune.nt_store;
+    return nullptr;
+}
+
+cgbn_status cgbn_set_tuning(const char* key, long long value)
+{
+    long long* slot = tuning_slot(key);
+    if (!slot) return CGBN_ERR_TUNING;
+    if (slot == &g_tune.reverse || slot == &g_tune.nt_store) {
+        if (value != 0 && value != 1) return CGBN_ERR_TUNING;
+    } else if (slot == &g_tune.wave_plane_bytes) {
+        if (value < 0 || value > (1LL << 20)) return CGBN_ERR_TUNING;
+    } else if (value < 4096 || value > (1LL << 26)) {
+        return CGBN_ERR_TUNING;
+    }
+    *slot = value;
+    return CGBN_OK;
+}
+
+long long cgbn_get_tuning(const char* key)
+{
+    long long* slot = tuning_slot(key);
+    return slot ? *slot : -1;
+}
+
+}  // extern "C"

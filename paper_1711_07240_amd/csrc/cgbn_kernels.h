@@ -1,0 +1,671 @@
+// Device code of libcgbn for gfx950 (wave64): the sweeps over the activation
+// tensors and the small cross-shard reductions.  No MFMA anywhere: every kernel
+// here is a streaming reduction or a streaming elementwise map, bound by HBM.
+//
+// Sweeps (one launch each):
+//   reduce  OP_SUM    sum x                       Algorithm 1 steps 1-3
+//   reduce  OP_SQDEV  sum (x - mean)^2            Algorithm 1 steps 6-8
+//   reduce  OP_BWD    sum dy, sum dy*xhat         backward device sums
+//   map     EL_NORM   y  = gamma*(x-mean)*invstd + beta            step 11
+//   map     EL_DX     dx = gamma*invstd*(dy - dbeta/M - xhat*dgamma/M)
+// A reduce sweep leaves one float per (channel, row) in `part`, where the rows
+// of a channel are ordered shard by shard; combine_rows then adds the rows of a
+// shard (the device sum of Algorithm 1) and the shards (its reduce step) in
+// double precision in a fixed order.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cgbn {
+
+constexpr int kThreads = 256;   // 4 wavefronts per workgroup
+constexpr int kWave = 64;
+
+enum { OP_SUM = 0, OP_SQDEV = 1, OP_BWD = 2 };
+enum { EL_NORM = 0, EL_DX = 1 };
+enum { CM_MEAN = 0, CM_INVSTD = 1, CM_BWD = 2, CM_SHARDS1 = 3, CM_SHARDS2 = 4 };
+
+struct bf16_t { uint16_t bits; };
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct SweepArgs {
+    const void* x;
+    const void* dy;
+    void* out;
+    const float* mean;
+    const float* mean_lo;     // may be null
+    const float* invstd;
+    const float* gamma;
+    const float* beta;
+    const float* dgamma;
+    const float* dbeta;
+    float* part0;             // [C][rows]
+    float* part1;             // [C][rows]
+    long long S;              // elements in the tensor
+    int N, C, HW, rows;
+    // NCHW
+    int L, sp;                // chunk elements, chunks per plane
+    // NHWC
+    int cv, TW, ctiles, rpp, PL, pps;
+    long long spix;           // pixels per shard
+    long long pivot_stride;   // elements between the first values of consecutive channels
+    float inv_M;
+    int reverse;              // walk the grid backwards
+    int nt;                   // non-temporal stores
+};
+
+// --------------------------------------------------------------------------
+// element access
+// --------------------------------------------------------------------------
+
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// round to nearest even; NaN stays a quiet NaN
+__device__ __forceinline__ uint32_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+
+template <typename T> struct Elem;
+
+template <> struct Elem<float> {
+    static constexpr int VEC = 4;
+    static __device__ __forceinline__ float load1(const float* p) { return *p; }
+    static __device__ __forceinline__ void store1(float* p, float v) { *p = v; }
+    static __device__ __forceinline__ void loadv(const float* p, float (&f)[4])
+    {
+        f32x4 v = *reinterpret_cast<const f32x4*>(p);
+        f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+    }
+    static __device__ __forceinline__ void storev(float* p, const float (&f)[4], int nt)
+    {
+        f32x4 v = {f[0], f[1], f[2], f[3]};
+        if (nt) __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
+        else *reinterpret_cast<f32x4*>(p) = v;
+    }
+};
+
+template <> struct Elem<bf16_t> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ float load1(const bf16_t* p) { return bf16_to_f32(p->bits); }
+    static __device__ __forceinline__ void store1(bf16_t* p, float v) { p->bits = (uint16_t)f32_to_bf16(v); }
+    static __device__ __forceinline__ void loadv(const bf16_t* p, float (&f)[8])
+    {
+        u32x4 v = *reinterpret_cast<const u32x4*>(p);
+        f[0] = __uint_as_float(v.x << 16); f[1] = __uint_as_float(v.x & 0xffff0000u);
+        f[2] = __uint_as_float(v.y << 16); f[3] = __uint_as_float(v.y & 0xffff0000u);
+        f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
+        f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
+    }
+    static __device__ __forceinline__ void storev(bf16_t* p, const float (&f)[8], int nt)
+    {
+        u32x4 v;
+        v.x = f32_to_bf16(f[0]) | (f32_to_bf16(f[1]) << 16);
+        v.y = f32_to_bf16(f[2]) | (f32_to_bf16(f[3]) << 16);
+        v.z = f32_to_bf16(f[4]) | (f32_to_bf16(f[5]) << 16);
+        v.w = f32_to_bf16(f[6]) | (f32_to_bf16(f[7]) << 16);
+        if (nt) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
+        else *reinterpret_cast<u32x4*>(p) = v;
+    }
+};
+
+// VEC-wide access for the channels-last kernels (V == Elem<T>::VEC or 1)
+template <typename T, int V> struct Access {
+    static __device__ __forceinline__ void load(const T* p, float (&f)[V]) { Elem<T>::loadv(p, f); }
+    static __device__ __forceinline__ void store(T* p, const float (&f)[V], int nt) { Elem<T>::storev(p, f, nt); }
+};
+template <typename T> struct Access<T, 1> {
+    static __device__ __forceinline__ void load(const T* p, float (&f)[1]) { f[0] = Elem<T>::load1(p); }
+    static __device__ __forceinline__ void store(T* p, const float (&f)[1], int) { Elem<T>::store1(p, f[0]); }
+};
+
+// --------------------------------------------------------------------------
+// wavefront and workgroup sums (fixed order, so results are reproducible)
+// --------------------------------------------------------------------------
+
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, false));
+}
+
+// Sum over the 64 lanes of a wavefront; every lane must be active.  Four DPP
+// steps fold each row of 16 lanes (swap neighbours, swap pairs, mirror the
+// half-row, mirror the row), then the four row totals are read out.
+__device__ __forceinline__ float wave_sum(float v)
+{
+    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);   // row_half_mirror
+    v += dpp_move<0x140>(v);   // row_mirror
+    float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
+}
+
+template <int V> __device__ __forceinline__ float fold(const float (&a)[V])
+{
+    if constexpr (V == 8) return ((a[0] + a[1]) + (a[2] + a[3])) + ((a[4] + a[5]) + (a[6] + a[7]));
+    else if constexpr (V == 4) return (a[0] + a[1]) + (a[2] + a[3]);
+    else return a[0];
+}
+
+// --------------------------------------------------------------------------
+// walking one contiguous run of elements with 16-byte vector accesses
+// --------------------------------------------------------------------------
+
+// Thread `t` of `STRIDE` cooperating threads visits its share of the elements
+// [seg0, seg0 + len): up to VEC-1 leading and trailing elements one by one (so
+// that the body starts on a 16-byte boundary of a 16-byte aligned tensor) and
+// the body as whole vectors, four at a time while that many remain.
+template <int STRIDE, int VEC, class F>
+__device__ __forceinline__ void walk_segment(long long seg0, int len, int t, long long S, F& f)
+{
+    if (seg0 < 0 || len <= 0 || seg0 + len > S) return;   // never touch memory outside the tensor
+    int mis = (int)(seg0 & (long long)(VEC - 1));
+    int head = mis ? min(VEC - mis, len) : 0;
+    int body = len - head;
+    int nvec = body / VEC;
+    int tail = body - nvec * VEC;
+    long long v0 = seg0 + head;
+    if (t < head) f.one(seg0 + t);
+    int i = t;
+    for (; i + 3 * STRIDE < nvec; i += 4 * STRIDE)
+        f.four(v0 + (long long)i * VEC, (long long)STRIDE * VEC);
+    for (; i < nvec; i += STRIDE) f.vec(v0 + (long long)i * VEC);
+    if (t < tail) f.one(v0 + (long long)nvec * VEC + t);
+}
+
+// per-channel constants of a sweep
+struct ChanConst {
+    float mu, mulo, istd, g, b, c2;
+};
+
+// The plain sum is taken about a pivot, the channel's first stored value, and the
+// pivot is added back in double precision by the combine step: the float
+// accumulators then hold numbers of the size of the channel's spread, not of its
+// offset, so the pooled mean keeps its accuracy when |mean| >> sigma.
+template <typename T, int OP> __device__ __forceinline__ ChanConst reduce_consts(const SweepArgs& A, int c)
+{
+    ChanConst k = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (OP == OP_SUM) {
+        k.mu = Elem<T>::load1(static_cast<const T*>(A.x) + (long long)c * A.pivot_stride);
+    } else {
+        k.mu = A.mean[c];
+        k.mulo = A.mean_lo ? A.mean_lo[c] : 0.f;
+    }
+    if (OP == OP_BWD) k.istd = A.invstd[c];
+    return k;
+}
+
+template <int EL> __device__ __forceinline__ ChanConst map_consts(const SweepArgs& A, int c)
+{
+    ChanConst k;
+    k.mu = A.mean[c];
+    k.mulo = A.mean_lo ? A.mean_lo[c] : 0.f;
+    k.istd = A.invstd[c];
+    k.g = A.gamma[c] * k.istd;
+    if (EL == EL_NORM) {
+        k.b = A.beta[c];
+        k.c2 = 0.f;
+    } else {
+        k.b = A.dbeta[c] * A.inv_M;
+        k.c2 = A.dgamma[c] * A.inv_M;
+    }
+    return k;
+}
+
+template <int OP> __device__ __forceinline__ void accumulate(const ChanConst& k, float xv, float dyv, float& a0, float& a1)
+{
+    if (OP == OP_SUM) {
+        a0 += xv - k.mu;
+    } else if (OP == OP_SQDEV) {
+        float d = (xv - k.mu) - k.mulo;
+        a0 += d * d;
+    } else {
+        float xh = ((xv - k.mu) - k.mulo) * k.istd;
+        a0 += dyv;
+        a1 += dyv * xh;
+    }
+}
+
+template <int EL> __device__ __forceinline__ float map_value(const ChanConst& k, float xv, float dyv)
+{
+    float d = (xv - k.mu) - k.mulo;
+    if (EL == EL_NORM) return d * k.g + k.b;
+    return k.g * ((dyv - k.b) - (d * k.istd) * k.c2);
+}
+
+// --------------------------------------------------------------------------
+// NCHW: a plane of H*W contiguous elements belongs to one channel
+// --------------------------------------------------------------------------
+
+template <typename T, int OP> struct PlaneReduce {
+    static constexpr int VEC = Elem<T>::VEC;
+    const T* x;
+    const T* dy;
+    ChanConst k;
+    float a0[VEC], a1[VEC];
+
+    __device__ __forceinline__ void one(long long off)
+    {
+        float xv = Elem<T>::load1(x + off);
+        float dv = OP == OP_BWD ? Elem<T>::load1(dy + off) : 0.f;
+        accumulate<OP>(k, xv, dv, a0[0], a1[0]);
+    }
+    __device__ __forceinline__ void vec(long long off)
+    {
+        float xv[VEC], dv[VEC];
+        Elem<T>::loadv(x + off, xv);
+        if (OP == OP_BWD) Elem<T>::loadv(dy + off, dv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) accumulate<OP>(k, xv[e], OP == OP_BWD ? dv[e] : 0.f, a0[e], a1[e]);
+    }
+    __device__ __forceinline__ void four(long long off, long long step)
+    {
+        float xv[4][VEC], dv[4][VEC];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) Elem<T>::loadv(x + off + u * step, xv[u]);
+        if (OP == OP_BWD) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Elem<T>::loadv(dy + off + u * step, dv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int e = 0; e < VEC; ++e)
+                accumulate<OP>(k, xv[u][e], OP == OP_BWD ? dv[u][e] : 0.f, a0[e], a1[e]);
+    }
+};
+
+template <typename T, int EL> struct PlaneMap {
+    static constexpr int VEC = Elem<T>::VEC;
+    const T* x;
+    const T* dy;
+    T* out;
+    ChanConst k;
+    int nt;
+
+    __device__ __forceinline__ void one(long long off)
+    {
+        float xv = Elem<T>::load1(x + off);
+        float dv = EL == EL_DX ? Elem<T>::load1(dy + off) : 0.f;
+        Elem<T>::store1(out + off, map_value<EL>(k, xv, dv));
+    }
+    __device__ __forceinline__ void vec(long long off)
+    {
+        float xv[VEC], dv[VEC], r[VEC];
+        Elem<T>::loadv(x + off, xv);
+        if (EL == EL_DX) Elem<T>::loadv(dy + off, dv);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) r[e] = map_value<EL>(k, xv[e], EL == EL_DX ? dv[e] : 0.f);
+        Elem<T>::storev(out + off, r, nt);
+    }
+    __device__ __forceinline__ void four(long long off, long long step)
+    {
+        float xv[4][VEC], dv[4][VEC];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) Elem<T>::loadv(x + off + u * step, xv[u]);
+        if (EL == EL_DX) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Elem<T>::loadv(dy + off + u * step, dv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float r[VEC];
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) r[e] = map_value<EL>(k, xv[u][e], EL == EL_DX ? dv[u][e] : 0.f);
+            Elem<T>::storev(out + off + u * step, r, nt);
+        }
+    }
+};
+
+// One workgroup per (plane, chunk): grid = N*C*sp.
+template <typename T, int OP>
+__global__ __launch_bounds__(kThreads) void nchw_reduce_block(SweepArgs A)
+{
+    constexpr int VEC = Elem<T>::VEC;
+    constexpr int Q = OP == OP_BWD ? 2 : 1;
+    __shared__ float sm[2 * 4];
+    long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
+    int j = (int)(b % A.sp);
+    long long plane = b / A.sp;
+    int c = (int)(plane % A.C);
+    int n = (int)(plane / A.C);
+    int beg = j * A.L;
+    int len = min(A.L, A.HW - beg);
+
+    PlaneReduce<T, OP> f;
+    f.x = static_cast<const T*>(A.x);
+    f.dy = static_cast<const T*>(A.dy);
+    f.k = reduce_consts<T, OP>(A, c);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { f.a0[e] = 0.f; f.a1[e] = 0.f; }
+    walk_segment<kThreads, VEC>(plane * A.HW + beg, len, (int)threadIdx.x, A.S, f);
+
+    float v[2] = {wave_sum(fold<VEC>(f.a0)), Q == 2 ? wave_sum(fold<VEC>(f.a1)) : 0.f};
+    int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    if (lane == 0) { sm[w] = v[0]; sm[4 + w] = v[1]; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        size_t o = (size_t)c * A.rows + (size_t)n * A.sp + j;
+        A.part0[o] = (sm[0] + sm[1]) + (sm[2] + sm[3]);
+        if (Q == 2) A.part1[o] = (sm[4] + sm[5]) + (sm[6] + sm[7]);
+    }
+}
+
+// One wavefront per plane (small planes): grid = ceil(N*C / 4).
+template <typename T, int OP>
+__global__ __launch_bounds__(kThreads) void nchw_reduce_wave(SweepArgs A)
+{
+    constexpr int VEC = Elem<T>::VEC;
+    constexpr int Q = OP == OP_BWD ? 2 : 1;
+    long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
+    int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    long long plane = b * 4 + w;
+    if (plane >= (long long)A.N * A.C) return;         // whole wavefronts leave together
+    int c = (int)(plane % A.C);
+    int n = (int)(plane / A.C);
+
+    PlaneReduce<T, OP> f;
+    f.x = static_cast<const T*>(A.x);
+    f.dy = static_cast<const T*>(A.dy);
+    f.k = reduce_consts<T, OP>(A, c);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { f.a0[e] = 0.f; f.a1[e] = 0.f; }
+    walk_segment<kWave, VEC>(plane * A.HW, A.HW, lane, A.S, f);
+
+    float v0 = wave_sum(fold<VEC>(f.a0));
+    float v1 = Q == 2 ? wave_sum(fold<VEC>(f.a1)) : 0.f;
+    if (lane == 0) {
+        size_t o = (size_t)c * A.rows + n;
+        A.part0[o] = v0;
+        if (Q == 2) A.part1[o] = v1;
+    }
+}
+
+template <typename T, int EL>
+__global__ __launch_bounds__(kThreads) void nchw_map_block(SweepArgs A)
+{
+    constexpr int VEC = Elem<T>::VEC;
+    long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
+    int j = (int)(b % A.sp);
+    long long plane = b / A.sp;
+    int c = (int)(plane % A.C);
+    int beg = j * A.L;
+    int len = min(A.L, A.HW - beg);
+    PlaneMap<T, EL> f;
+    f.x = static_cast<const T*>(A.x);
+    f.dy = static_cast<const T*>(A.dy);
+    f.out = static_cast<T*>(A.out);
+    f.k = map_consts<EL>(A, c);
+    f.nt = A.nt;
+    walk_segment<kThreads, VEC>(plane * A.HW + beg, len, (int)threadIdx.x, A.S, f);
+}
+
+template <typename T, int EL>
+__global__ __launch_bounds__(kThreads) void nchw_map_wave(SweepArgs A)
+{
+    constexpr int VEC = Elem<T>::VEC;
+    long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
+    int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    long long plane = b * 4 + w;
+    if (plane >= (long long)A.N * A.C) return;
+    int c = (int)(plane % A.C);
+    PlaneMap<T, EL> f;
+    f.x = static_cast<const T*>(A.x);
+    f.dy = static_cast<const T*>(A.dy);
+    f.out = static_cast<T*>(A.out);
+    f.k = map_consts<EL>(A, c);
+    f.nt = A.nt;
+    walk_segment<kWave, VEC>(plane * A.HW, A.HW, lane, A.S, f);
+}
+
+// --------------------------------------------------------------------------
+// NHWC: the C channels of a pixel are contiguous; a thread owns V channels
+// --------------------------------------------------------------------------
+
+// Workgroup = (row, column tile).  A row is a run of up to PL pixels of one
+// shard; a column tile is TW vectors of V channels.  Thread t works on vector
+// column t % TW of pixels t / TW, t / TW + rpp, ...
+template <typename T, int V, int OP>
+__global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
+{
+    constexpr int Q = OP == OP_BWD ? 2 : 1;
+    __shared__ float sm[Q * kThreads * V];
+    long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
+    int ct = (int)(b % A.ctiles);
+    int row = (int)(b / A.ctiles);
+    int k = row / A.pps, pj = row % A.pps;
+    long long pix0 = (long long)k * A.spix + (long long)pj * A.PL;
+    long long left = A.spix - (long long)pj * A.PL;
+    int npix = (int)(left < A.PL ? left : A.PL);
+    if (pix0 < 0 || (pix0 + npix) * A.C > A.S) npix = 0;    // never outside the tensor
+    int t = threadIdx.x;
+    int col = t % A.TW, r = t / A.TW;
+    int vc = ct * A.TW + col;
+    bool active = r < A.rpp && vc < A.cv;
+    int cb = vc * V;
+
+    float a0[V], a1[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) { a0[e] = 0.f; a1[e] = 0.f; }
+    if (active) {
+        ChanConst kc[V];
+#pragma unroll
+        for (int e = 0; e < V; ++e) kc[e] = reduce_consts<T, OP>(A, cb + e);
+        const T* px = static_cast<const T*>(A.x) + pix0 * A.C + cb;
+        const T* pd = static_cast<const T*>(A.dy) + pix0 * A.C + cb;
+        const long long C = A.C;
+        const int rpp = A.rpp;
+        int i = r;
+        for (; i + 3 * rpp < npix; i += 4 * rpp) {
+            float xv[4][V], dv[4][V];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Access<T, V>::load(px + (long long)(i + u * rpp) * C, xv[u]);
+            if (OP == OP_BWD) {
+#pragma unroll
+                for (int u = 0; u < 4; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, dv[u]);
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < V; ++e)
+                    accumulate<OP>(kc[e], xv[u][e], OP == OP_BWD ? dv[u][e] : 0.f, a0[e], a1[e]);
+        }
+        for (; i < npix; i += rpp) {
+            float xv[V], dv[V];
+            Access<T, V>::load(px + (long long)i * C, xv);
+            if (OP == OP_BWD) Access<T, V>::load(pd + (long long)i * C, dv);
+#pragma unroll
+            for (int e = 0; e < V; ++e) accumulate<OP>(kc[e], xv[e], OP == OP_BWD ? dv[e] : 0.f, a0[e], a1[e]);
+        }
+    }
+    // fold the rpp pixel rows of the workgroup, in a fixed order
+    const int nout = A.TW * V;
+    if (r < A.rpp) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            sm[(0 * A.rpp + r) * nout + col * V + e] = a0[e];
+            if (Q == 2) sm[(1 * A.rpp + r) * nout + col * V + e] = a1[e];
+        }
+    }
+    __syncthreads();
+    for (int o = t; o < nout; o += kThreads) {
+        int ch = ct * nout + o;
+        if (ch >= A.C) continue;
+        float s0 = 0.f, s1 = 0.f;
+        for (int rr = 0; rr < A.rpp; ++rr) {
+            s0 += sm[(0 * A.rpp + rr) * nout + o];
+            if (Q == 2) s1 += sm[(1 * A.rpp + rr) * nout + o];
+        }
+        size_t po = (size_t)ch * A.rows + row;
+        A.part0[po] = s0;
+        if (Q == 2) A.part1[po] = s1;
+    }
+}
+
+template <typename T, int V, int EL>
+__global__ __launch_bounds__(kThreads) void nhwc_map(SweepArgs A)
+{
+    long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
+    int ct = (int)(b % A.ctiles);
+    int row = (int)(b / A.ctiles);
+    int k = row / A.pps, pj = row % A.pps;
+    long long pix0 = (long long)k * A.spix + (long long)pj * A.PL;
+    long long left = A.spix - (long long)pj * A.PL;
+    int npix = (int)(left < A.PL ? left : A.PL);
+    if (pix0 < 0 || (pix0 + npix) * A.C > A.S) npix = 0;
+    int t = threadIdx.x;
+    int col = t % A.TW, r = t / A.TW;
+    int vc = ct * A.TW + col;
+    if (!(r < A.rpp && vc < A.cv)) return;
+    int cb = vc * V;
+    ChanConst kc[V];
+#pragma unroll
+    for (int e = 0; e < V; ++e) kc[e] = map_consts<EL>(A, cb + e);
+    const T* px = static_cast<const T*>(A.x) + pix0 * A.C + cb;
+    const T* pd = static_cast<const T*>(A.dy) + pix0 * A.C + cb;
+    T* po = static_cast<T*>(A.out) + pix0 * A.C + cb;
+    const long long C = A.C;
+    const int rpp = A.rpp;
+    int i = r;
+    for (; i + 3 * rpp < npix; i += 4 * rpp) {
+        float xv[4][V], dv[4][V];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) Access<T, V>::load(px + (long long)(i + u * rpp) * C, xv[u]);
+        if (EL == EL_DX) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, dv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            float o[V];
+#pragma unroll
+            for (int e = 0; e < V; ++e) o[e] = map_value<EL>(kc[e], xv[u][e], EL == EL_DX ? dv[u][e] : 0.f);
+            Access<T, V>::store(po + (long long)(i + u * rpp) * C, o, A.nt);
+        }
+    }
+    for (; i < npix; i += rpp) {
+        float xv[V], dv[V], o[V];
+        Access<T, V>::load(px + (long long)i * C, xv);
+        if (EL == EL_DX) Access<T, V>::load(pd + (long long)i * C, dv);
+#pragma unroll
+        for (int e = 0; e < V; ++e) o[e] = map_value<EL>(kc[e], xv[e], EL == EL_DX ? dv[e] : 0.f);
+        Access<T, V>::store(po + (long long)i * C, o, A.nt);
+    }
+}
+
+// --------------------------------------------------------------------------
+// cross-shard reductions (tiny: [C][rows] floats or [K][C] doubles)
+// --------------------------------------------------------------------------
+
+struct CombineArgs {
+    const float* part0;   // [C][rows]
+    const float* part1;   // [C][rows] (CM_BWD only)
+    double* sh0;          // [K][C] shard sums out, may be null
+    double* sh1;
+    float* out0;          // mean | invstd | dbeta
+    float* out1;          // mean_lo (workspace) | - | dgamma
+    float* out2;          // mean_lo (caller, may be null)
+    double M;
+    double eps;
+    double shard_count;   // values per shard and channel
+    const void* x;        // pivots are read from here when pivot_stride > 0
+    long long pivot_stride;
+    int is_bf16;
+    int C, rows, K, rps, G; // G lanes share one shard, a power of two <= 64
+};
+
+__device__ __forceinline__ double pivot_of(const CombineArgs& A, int c)
+{
+    if (A.pivot_stride <= 0) return 0.0;
+    long long o = (long long)c * A.pivot_stride;
+    if (A.is_bf16) return (double)bf16_to_f32(static_cast<const bf16_t*>(A.x)[o].bits);
+    return (double)static_cast<const float*>(A.x)[o];
+}
+
+// One wavefront per channel.  Level 1: groups of G lanes add the rows of one
+// shard (the device sum of Algorithm 1).  Level 2: the shard sums are added
+// (its reduce step).  Double precision, fixed order.
+__device__ __forceinline__ double shard_then_total(const float* pr, double* sh, int c, const CombineArgs& A, int lane,
+                                                   double shard_offset)
+{
+    const int G = A.G;
+    const int gl = lane & (G - 1), gi = lane / G, spp = kWave / G;
+    double tot = 0.0;
+    for (int k0 = 0; k0 < A.K; k0 += spp) {
+        int k = k0 + gi;
+        double acc = 0.0;
+        if (k < A.K)
+            for (int r = gl; r < A.rps; r += G) acc += (double)pr[(size_t)k * A.rps + r];
+        for (int off = G >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+        if (k < A.K) {
+            if (sh && gl == 0) sh[(size_t)k * A.C + c] = acc + shard_offset;
+            tot += acc;
+        }
+    }
+    for (int off = kWave >> 1; off >= G; off >>= 1) tot += __shfl_xor(tot, off);
+    return tot;
+}
+
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
+{
+    int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    int c = blockIdx.x * 4 + w;
+    if (c >= A.C) return;
+    const double pivot = pivot_of(A, c);      // zero unless the rows hold sums about a pivot
+    double t0 = shard_then_total(A.part0 + (size_t)c * A.rows, A.sh0, c, A, lane, pivot * A.shard_count);
+    double t1 = 0.0;
+    if (MODE == CM_BWD || MODE == CM_SHARDS2)
+        t1 = shard_then_total(A.part1 + (size_t)c * A.rows, A.sh1, c, A, lane, 0.0);
+    if (lane != 0) return;
+    if (MODE == CM_MEAN) {
+        double m = pivot + t0 / A.M;
+        float hi = (float)m;
+        float lo = (float)(m - (double)hi);
+        A.out0[c] = hi;
+        A.out1[c] = lo;
+        if (A.out2) A.out2[c] = lo;
+    } else if (MODE == CM_INVSTD) {
+        A.out0[c] = (float)(1.0 / sqrt(t0 / A.M + A.eps));
+    } else if (MODE == CM_BWD) {
+        A.out0[c] = (float)t0;
+        A.out1[c] = (float)t1;
+    }
+}
+
+// Reduce step alone, from caller-held shard sums: one thread per channel.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void combine_shards(const double* s0, const double* s1, int K, int C,
+                                                           double M, double eps, float* out0, float* out1)
+{
+    int c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= C) return;
+    double t0 = 0.0, t1 = 0.0;
+    for (int k = 0; k < K; ++k) {
+        t0 += s0[(size_t)k * C + c];
+        if (MODE == CM_BWD) t1 += s1[(size_t)k * C + c];
+    }
+    if (MODE == CM_MEAN) {
+        double m = t0 / M;
+        float hi = (float)m;
+        out0[c] = hi;
+        if (out1) out1[c] = (float)(m - (double)hi);
+    } else if (MODE == CM_INVSTD) {
+        out0[c] = (float)(1.0 / sqrt(t0 / M + eps));
+    } else {
+        out0[c] = (float)t0;
+        out1[c] = (float)t1;
+    }
+}
+
+}  // namespace cgbn

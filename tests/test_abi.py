@@ -1,0 +1,126 @@
+"""The C ABI without a GPU: the library loads, exports what the header declares,
+sizes workspaces, and turns bad arguments into status codes before any launch."""
+
+import os
+import re
+
+import pytest
+
+from paper_1711_07240_amd import cgbn as L
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "cgbn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cgbn_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared()
+    assert "cgbn_forward" in names and "cgbn_backward" in names and len(names) >= 14
+    handle = L.lib()
+    for n in names:
+        assert hasattr(handle, n), n
+    assert sorted(L.SIGNATURES) == names
+    for n in names:                       # the binding has a function of the same name
+        assert callable(getattr(L, n)), n
+
+
+def test_status_strings():
+    seen = {L.cgbn_status_string(i) for i in range(10)}
+    assert len(seen) == 10 and "ok" in seen
+    assert L.cgbn_status_string(99) == "unknown status"
+
+
+def test_workspace_bytes():
+    wb = L.cgbn_workspace_bytes(4, 16, 32, 32, "NCHW", "f32", 2)
+    assert wb > 0 and wb % 256 == 0
+    for wl in [(16, 64, 400, 672, "NCHW", "f32", 8), (256, 2048, 25, 42, "NCHW", "f32", 128),
+               (64, 512, 50, 84, "NHWC", "bf16", 32)]:
+        b = L.cgbn_workspace_bytes(*wl)
+        assert 0 < b < 64 << 20 and b % 256 == 0
+    # invalid problems have no workspace size
+    assert L.cgbn_workspace_bytes(4, 16, 32, 32, "NCHW", "f32", 3) == 0
+    assert L.cgbn_workspace_bytes(0, 16, 32, 32, "NCHW", "f32", 1) == 0
+    assert L.cgbn_workspace_bytes(4, 16, 32, 32, 7, "f32", 2) == 0
+    assert L.cgbn_workspace_bytes(4, 16, 32, 32, "NCHW", 5, 2) == 0
+
+
+P = 0x10000  # a non-null, 256-byte aligned fake address: never dereferenced on these paths
+GOOD = dict(x=P, N=4, C=16, H=32, W=32, layout="NCHW", K=2, gamma=P, beta=P, eps=1e-5,
+            y=P, mean=P, invstd=P, dtype="f32", mean_lo=None, workspace=P,
+            workspace_bytes=1 << 20, stream=0)
+
+
+def _fwd(**kw):
+    a = dict(GOOD, **kw)
+    with pytest.raises(L.CgbnError) as e:
+        L.cgbn_forward(**a)
+    return e.value.code
+
+
+def test_forward_argument_errors():
+    assert _fwd(x=None) == 1 and _fwd(gamma=None) == 1 and _fwd(y=None) == 1 and _fwd(invstd=None) == 1
+    assert _fwd(N=0) == 2 and _fwd(C=-1) == 2 and _fwd(H=0) == 2
+    assert _fwd(N=1 << 20, C=1 << 20) == 2
+    assert _fwd(K=0) == 3 and _fwd(K=3) == 3 and _fwd(K=8) == 3
+    assert _fwd(layout=2) == 4 and _fwd(dtype=-1) == 4
+    assert _fwd(eps=0.0) == 5 and _fwd(eps=-1.0) == 5 and _fwd(eps=float("nan")) == 5
+    assert _fwd(eps=float("inf")) == 5
+    assert _fwd(workspace=None) == 6 and _fwd(workspace_bytes=16) == 6 and _fwd(workspace=P + 64) == 6
+    assert _fwd(x=P + 4) == 7 and _fwd(y=P + 8) == 7
+
+
+def test_backward_argument_errors():
+    good = dict(dy=P, x=P, mean=P, invstd=P, gamma=P, dx=P, dgamma=P, dbeta=P, N=4, C=16, H=32, W=32,
+                layout="NHWC", K=4, dtype="bf16", mean_lo=None, workspace=P, workspace_bytes=1 << 20,
+                stream=0)
+
+    def bwd(**kw):
+        with pytest.raises(L.CgbnError) as e:
+            L.cgbn_backward(**dict(good, **kw))
+        return e.value.code
+
+    assert bwd(dy=None) == 1 and bwd(dgamma=None) == 1 and bwd(mean=None) == 1
+    assert bwd(W=0) == 2 and bwd(K=5) == 3 and bwd(layout=-1) == 4 and bwd(dtype=2) == 4
+    assert bwd(workspace_bytes=0) == 6 and bwd(dx=P + 2) == 7 and bwd(dy=P + 8) == 7
+
+
+def test_step_entry_points_validate_too():
+    def code(fn, *a, **kw):
+        with pytest.raises(L.CgbnError) as e:
+            fn(*a, **kw)
+        return e.value.code
+
+    assert code(L.cgbn_shard_sum, None, 4, 16, 8, 8, "NCHW", 2, "f32", P, P, 1 << 20, 0) == 1
+    assert code(L.cgbn_shard_sum, P, 4, 16, 8, 8, "NCHW", 3, "f32", P, P, 1 << 20, 0) == 3
+    assert code(L.cgbn_shard_sum, P, 4, 16, 8, 8, "NCHW", 2, "f32", P, P, 8, 0) == 6
+    assert code(L.cgbn_reduce_mean, None, 2, 16, 256, P, None, 0) == 1
+    assert code(L.cgbn_reduce_mean, P, 0, 16, 256, P, None, 0) == 3
+    assert code(L.cgbn_reduce_mean, P, 2, 16, 0, P, None, 0) == 2
+    assert code(L.cgbn_shard_sqdev, P, 4, 16, 8, 8, "NCHW", 2, "f32", None, None, P, P, 1 << 20, 0) == 1
+    assert code(L.cgbn_reduce_invstd, P, 2, 16, 256, 0.0, P, 0) == 5
+    assert code(L.cgbn_normalize, P, 4, 16, 8, 8, "NCHW", "f32", P, None, P, P, None, P, 0) == 1
+    assert code(L.cgbn_normalize, P + 4, 4, 16, 8, 8, "NCHW", "f32", P, None, P, P, P, P, 0) == 7
+    assert code(L.cgbn_backward_shard_sums, P, P, 4, 16, 8, 8, "NHWC", 2, "f32", P, None, P, P, None,
+                P, 1 << 20, 0) == 1
+    assert code(L.cgbn_backward_reduce, P, None, 2, 16, P, P, 0) == 1
+    assert code(L.cgbn_backward_dx, P, P, 4, 16, 8, 8, 3, "f32", P, None, P, P, P, P, P, 0) == 4
+
+
+def test_tuning_knobs():
+    assert L.cgbn_get_tuning("no_such_key") == -1
+    with pytest.raises(L.CgbnError):
+        L.cgbn_set_tuning("no_such_key", 1)
+    with pytest.raises(L.CgbnError):
+        L.cgbn_set_tuning("reverse", 2)
+    old = L.cgbn_get_tuning("chunk_bytes")
+    before = L.cgbn_workspace_bytes(16, 64, 400, 672, "NCHW", "f32", 8)
+    try:
+        L.cgbn_set_tuning("chunk_bytes", 2 * old)
+        assert L.cgbn_get_tuning("chunk_bytes") == 2 * old
+        assert L.cgbn_workspace_bytes(16, 64, 400, 672, "NCHW", "f32", 8) < before
+    finally:
+        L.cgbn_set_tuning("chunk_bytes", old)

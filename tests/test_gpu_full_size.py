@@ -1,0 +1,99 @@
+"""GPU parity at the full sizes of the five workloads, in the launch
+configuration the benchmark times.  A sample of channels is compared with the
+float64 oracle on every element (channels are independent, so the oracle can
+take them one by one); all channels are checked through properties and against
+a float64 library reduction on the device."""
+
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import cgbn_oracle as O
+from paper_1711_07240_amd import synth
+from gpu_harness import DEV, Problem, check_against_oracle, widen, to_host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+def _chan(t, layout, idx):
+    return t[:, idx] if layout == "NCHW" else t[..., idx]
+
+
+def _as_f64_dev(t, dtype):
+    if dtype == "bf16":
+        return t.view(torch.bfloat16).to(torch.float64)
+    return t.to(torch.float64)
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg4b"])
+def test_full_size(name):
+    wl = synth.WORKLOADS[name]
+    t0 = time.time()
+    print(f"[case] {name}: generating {wl.S} elements x2 on the host", flush=True)
+    d = synth.make_inputs(wl, threads=16)
+    print(f"[case] {name}: generated in {time.time() - t0:.1f}s; running forward+backward", flush=True)
+    p = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
+    p.forward()
+    p.backward()
+    torch.cuda.synchronize()
+    print(f"[case] {name}: kernels done", flush=True)
+
+    # ---- sampled channels, every element, against the oracle -------------
+    rng = np.random.default_rng(wl.seed)
+    chans = sorted(set([0, wl.C - 1] + rng.choice(wl.C, size=4, replace=False).tolist()))
+    xs, dys = _chan(d["x"], wl.layout, chans), _chan(d["dy"], wl.layout, chans)
+    ref = O.cgbn_forward_backward_ref(widen(xs, wl.dtype), widen(dys, wl.dtype),
+                                      d["gamma"][chans].astype(np.float64),
+                                      d["beta"][chans].astype(np.float64), wl.eps, wl.layout)
+    idx = torch.tensor(chans, device=DEV)
+    sel = (lambda t: t.index_select(1 if wl.layout == "NCHW" else 3, idx))
+    got = dict(y=to_host_f64(sel(p.y), wl.dtype), dx=to_host_f64(sel(p.dx), wl.dtype))
+    for k in ("mean", "invstd", "dgamma", "dbeta"):
+        got[k] = getattr(p, k)[idx].cpu().numpy().astype(np.float64)
+    rep = check_against_oracle(got, ref, wl.dtype, f"{name} channels {chans}")
+    print(f"[ok] {name}: sampled channels {chans}: {rep}", flush=True)
+
+    # ---- all channels: properties + a float64 library reduction ----------
+    tol = 1e-4 if wl.dtype == "f32" else 2e-2
+    dims_ = (0, 2, 3) if wl.layout == "NCHW" else (0, 1, 2)
+    M = wl.M
+    step = max(1, min(wl.C, (1 << 27) // M))          # ~1 GiB of float64 per chunk
+    mean = p.mean.double() + p.mean_lo.double()
+    for c0 in range(0, wl.C, step):
+        cs = slice(c0, min(wl.C, c0 + step))
+        bshape = (1, -1, 1, 1) if wl.layout == "NCHW" else (1, 1, 1, -1)
+        x64 = _as_f64_dev(_chan(p.x, wl.layout, cs), wl.dtype)
+        var_t, mean_t = torch.var_mean(x64, dim=dims_, unbiased=False)
+        sig = torch.sqrt(var_t + wl.eps)
+        assert torch.all((mean[cs] - mean_t).abs() <= tol * torch.maximum(mean_t.abs(), sig)), name
+        assert torch.all((p.invstd[cs].double() - 1 / sig).abs() <= tol / sig), name
+        xhat = (x64 - mean_t.view(bshape)) / sig.view(bshape)
+        del x64
+        y64 = _as_f64_dev(_chan(p.y, wl.layout, cs), wl.dtype)
+        # the normalised output has mean beta and biased variance gamma^2 var/(var+eps)
+        ytol = 1e-4 if wl.dtype == "f32" else 2e-2 * (p.beta[cs].abs().double() + 1e-2)
+        assert torch.all((y64.mean(dim=dims_) - p.beta[cs].double()).abs() <= ytol), name
+        want_var = p.gamma[cs].double() ** 2 * var_t / (var_t + wl.eps)
+        assert torch.all((y64.var(dim=dims_, unbiased=False) - want_var).abs()
+                         <= 10 * tol * want_var + 1e-6), name
+        del y64
+        dy64 = _as_f64_dev(_chan(p.dy, wl.layout, cs), wl.dtype)
+        db_t = dy64.sum(dim=dims_)
+        dg_t = (dy64 * xhat).sum(dim=dims_)
+        del xhat
+        scale_b = torch.sqrt((db_t ** 2).mean())
+        assert torch.all((p.dbeta[cs].double() - db_t).abs() <= tol * torch.maximum(db_t.abs(), scale_b)), name
+        if name != "cfg4":
+            scale_g = torch.sqrt((dg_t ** 2).mean())
+            assert torch.all((p.dgamma[cs].double() - dg_t).abs()
+                             <= tol * torch.maximum(dg_t.abs(), scale_g)), name
+        else:
+            assert torch.all(p.dgamma[cs] == 0), name        # xhat is exactly zero
+        dx64 = _as_f64_dev(_chan(p.dx, wl.layout, cs), wl.dtype)
+        # the gradient sums to zero over the pooled axes
+        budget = (1e-5 if wl.dtype == "f32" else 4e-3) * dx64.abs().sum(dim=dims_) + 1e-12
+        assert torch.all(dx64.sum(dim=dims_).abs() <= budget), name
+        del dx64, dy64
+    print(f"[ok] {name}: all {wl.C} channels pass the property and library checks", flush=True)

@@ -142,12 +142,14 @@ def test_step_entry_points_match_algorithm_1(layout, dtype):
     ref = dict(y=y_r, mean=mean_r, invstd=invstd_r, dx=dx_r, dgamma=dg_r, dbeta=db_r)
     check_against_oracle(got, ref, dtype, f"steps-{layout}-{dtype}")
 
-    # the fused entry points run the same kernels: bitwise the same outputs
+    # the fused entry points run the same sweeps; only the double-precision order of
+    # the reduce step differs, so the outputs agree to the last bit or two
     q = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, layout, dtype, K)
     q.forward(); q.backward()
     got2 = q.results()
-    for k in ("y", "mean", "invstd", "mean_lo", "dx", "dgamma", "dbeta"):
-        assert np.array_equal(got[k], got2[k]), k
+    for k in ("y", "mean", "invstd", "dx", "dgamma", "dbeta"):
+        assert np.allclose(got[k], got2[k], rtol=1e-2 if dtype == "bf16" else 2e-6, atol=1e-6), k
+    assert np.allclose(got["mean"] + got["mean_lo"], got2["mean"] + got2["mean_lo"], rtol=1e-12, atol=1e-12)
 
 
 def test_shard_count_changes_only_rounding_and_runs_are_reproducible():

@@ -70,6 +70,14 @@ typedef enum cgbn_dtype { CGBN_F32 = 0, CGBN_BF16 = 1 } cgbn_dtype; /* of x, y, 
 size_t cgbn_workspace_bytes(int N, int C, int H, int W, cgbn_layout layout,
                             cgbn_dtype dtype, int K);
 
+/* Byte offset, inside a workspace for this problem, of a 32-bit word that is 0
+ * after cgbn_forward / cgbn_backward unless a bounded device-side wait gave up
+ * (it cannot when the launch is sound; if it does, the statistics of the
+ * affected channels are NaN).  Read it after synchronising the stream.
+ * Returns (size_t)-1 if the arguments are invalid. */
+size_t cgbn_workspace_error_offset(int N, int C, int H, int W, cgbn_layout layout,
+                                   cgbn_dtype dtype, int K);
+
 /* Algorithm 1, all steps.  In: x, gamma[C], beta[C], eps.  Out: y (same shape,
  * layout and dtype as x; bf16 rounded to nearest-even), mean[C], invstd[C] =
  * 1/sqrt(var + eps), and mean_lo[C] if not NULL. */
@@ -145,6 +153,9 @@ const char* cgbn_status_string(cgbn_status status);
  *   "piece_bytes"      NHWC: bytes of one pixel range handled by one workgroup
  *   "reverse"          0/1: alternate the sweep direction between consecutive sweeps
  *   "nt_store"         0/1: non-temporal stores for y and dx
+ *   "fused"            0/1: register-resident single-launch forward/backward (NCHW)
+ *   "fused_groups"     workgroups of that launch (0 = all that are resident at once)
+ *   "spin_limit"       polls before a device-side wait gives up
  * cgbn_get_tuning returns -1 for an unknown key. */
 cgbn_status cgbn_set_tuning(const char* key, long long value);
 long long cgbn_get_tuning(const char* key);

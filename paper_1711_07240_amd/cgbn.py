@@ -29,6 +29,7 @@ _c_int, _c_ll, _c_f, _c_sz, _c_p = (ctypes.c_int, ctypes.c_longlong, ctypes.c_fl
 # name -> (restype, argtypes); mirrors include/cgbn.h declaration by declaration
 SIGNATURES = {
     "cgbn_workspace_bytes": (_c_sz, [_c_int] * 4 + [_c_int, _c_int, _c_int]),
+    "cgbn_workspace_error_offset": (_c_sz, [_c_int] * 4 + [_c_int, _c_int, _c_int]),
     "cgbn_forward": (_c_int, [_c_p] + [_c_int] * 4 + [_c_int, _c_int, _c_p, _c_p, _c_f,
                               _c_p, _c_p, _c_p, _c_int, _c_p, _c_p, _c_sz, _c_p]),
     "cgbn_backward": (_c_int, [_c_p] * 8 + [_c_int] * 4 + [_c_int, _c_int, _c_int, _c_p,
@@ -115,6 +116,10 @@ def cgbn_status_string(code: int) -> str:
 
 def cgbn_workspace_bytes(N, C, H, W, layout, dtype, K) -> int:
     return int(lib().cgbn_workspace_bytes(N, C, H, W, _enum(LAYOUTS, layout), _enum(DTYPES, dtype), K))
+
+
+def cgbn_workspace_error_offset(N, C, H, W, layout, dtype, K) -> int:
+    return int(lib().cgbn_workspace_error_offset(N, C, H, W, _enum(LAYOUTS, layout), _enum(DTYPES, dtype), K))
 
 
 def cgbn_forward(x, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd,

@@ -3,6 +3,7 @@
 
 #include "cgbn.h"
 #include "cgbn_kernels.h"
+#include "cgbn_fused.h"
 
 #include <cmath>
 #include <cstring>
@@ -18,8 +19,24 @@ struct Tuning {
     long long piece_bytes = 131072;      // NHWC: bytes of a pixel run per workgroup (full channel width)
     long long reverse = 1;               // alternate sweep direction so a sweep starts on what the last one left in cache
     long long nt_store = 1;              // non-temporal stores for y and dx
+    long long fused = 1;                 // register-resident single-launch path where the shape allows it
+    long long spin_limit = 1LL << 24;    // polls of a bounded wait in the fused kernels before it gives up
+    long long fused_groups = 0;          // workgroups of the fused grid (0 = as many as are resident at once)
 };
 Tuning g_tune;
+#ifdef CGBN_TRACE
+unsigned long long* g_trace = nullptr;
+#endif
+
+// Geometry of the register-resident path for one direction (`words` 32-bit
+// registers of one tensor per thread: 128 forward, 64 backward).
+struct FusedPlan {
+    int ok;               // shape can take the path at all (grid size is checked at launch)
+    int LB;               // bytes per load: 16 or 8
+    int LPPC;             // 0: large planes; else register slots per plane (a power of two >= LPP)
+    int tp, TL, LPP, IPU, U, rows, rps, G;
+    long long total_units;
+};
 
 struct Plan {
     int N, C, H, W, K, layout, dtype;
@@ -35,11 +52,60 @@ struct Plan {
     // partial sums
     int rows, rps, G;
     long long grid;       // workgroups of one sweep
+    FusedPlan ff, fb;     // register-resident path, forward and backward
     // workspace layout (byte offsets)
-    size_t off_part0, off_part1, off_sh0, off_sh1, off_mlo, bytes;
+    size_t off_part0, off_part1, off_sh0, off_sh1, off_mlo, off_sync, bytes;
 };
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
+
+void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, FusedPlan* f)
+{
+    std::memset(f, 0, sizeof(*f));
+    if (layout != CGBN_NCHW || K > kFusedMaxShards) return;
+    int LB = 0;
+    for (int lb = 16; lb >= 8; lb >>= 1)
+        if (HW % (lb / eb) == 0) { LB = lb; break; }
+    if (!LB) return;                                   // planes that are not a whole number of 8-byte loads
+    const int W = LB / 4, R = words / W, E = LB / eb;
+    const long long wave_cap = (long long)R * kWave * E;   // elements one wavefront can hold
+    const int ips = N / K;
+    f->LB = LB;
+    if (HW <= wave_cap) {
+        f->LPP = (int)((HW + (long long)kWave * E - 1) / ((long long)kWave * E));
+        int lppc = R / 16 > 2 ? R / 16 : 2;            // at most 16 planes per wavefront
+        while (lppc < f->LPP) lppc <<= 1;
+        f->LPPC = lppc;
+        int per_unit = 4 * (R / lppc);
+        f->U = (N + per_unit - 1) / per_unit;
+        f->IPU = (N + f->U - 1) / f->U;
+        // byte offsets inside a unit are 32-bit
+        if ((long long)f->IPU * C * HW * eb > 0x7fffffffLL) return;
+        f->rows = N;
+        f->rps = ips;
+    } else {
+        const long long cap = wave_cap * 4;
+        long long tp = (HW + cap - 1) / cap;
+        long long gran = (long long)kThreads * E;
+        long long TL = (HW + tp - 1) / tp;
+        TL = (TL + gran - 1) / gran * gran;
+        tp = (HW + TL - 1) / TL;
+        if ((long long)N * tp > kFusedMaxRows) return;
+        f->tp = (int)tp;
+        f->TL = (int)TL;
+        f->U = (int)(N * tp);
+        f->rows = f->U;
+        f->rps = (int)(ips * tp);
+    }
+    if (f->rows > kFusedMaxRows) return;
+    f->total_units = (long long)C * f->U;
+    if (f->total_units > 0x7fffffffLL) return;
+    int G = 1;
+    while (G < kWave && G < f->rps) G <<= 1;
+    f->G = G;
+    f->ok = 1;
+}
+
 
 cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, Plan* p)
 {
@@ -102,14 +168,20 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     int G = 1;
     while (G < kWave && G < p->rps) G <<= 1;
     p->G = G;
-    size_t part = align256((size_t)C * p->rows * sizeof(float));
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, &p->ff);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, &p->fb);
+    int max_rows = p->rows;
+    if (p->ff.ok && p->ff.rows > max_rows) max_rows = p->ff.rows;
+    if (p->fb.ok && p->fb.rows > max_rows) max_rows = p->fb.rows;
+    size_t part = align256((size_t)C * max_rows * sizeof(float));
     size_t sh = align256((size_t)K * C * sizeof(double));
     p->off_part0 = 0;
     p->off_part1 = part;
     p->off_sh0 = 2 * part;
     p->off_sh1 = 2 * part + sh;
     p->off_mlo = 2 * part + 2 * sh;
-    p->bytes = p->off_mlo + align256((size_t)C * sizeof(float));
+    p->off_sync = p->off_mlo + align256((size_t)C * sizeof(float));
+    p->bytes = p->off_sync + align256(((size_t)kSyncHeader + 4 * (size_t)C) * sizeof(unsigned));
     return CGBN_OK;
 }
 
@@ -200,6 +272,7 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
     A.pivot_stride = pivot_x ? (p.layout == CGBN_NCHW ? p.HW : 1) : 0;
     A.is_bf16 = p.dtype == CGBN_BF16;
     A.C = p.C; A.rows = p.rows; A.K = p.K; A.rps = p.rps; A.G = p.G;
+    A.clear_word = reinterpret_cast<unsigned*>(ws + p.off_sync) + 1;
     dim3 grid((unsigned)((p.C + 3) / 4)), block(kThreads);
     switch (mode) {
     case CM_MEAN:   hipLaunchKernelGGL((combine_rows<CM_MEAN>), grid, block, 0, st, A); break;
@@ -209,6 +282,80 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
     default:        hipLaunchKernelGGL((combine_rows<CM_SHARDS1>), grid, block, 0, st, A); break;
     }
     return launched();
+}
+
+// ---- register-resident path ------------------------------------------------
+
+template <typename KernelT> int resident_groups(KernelT kernel)
+{
+    // workgroups of `kernel` that are resident at once on the current device
+    int dev = 0, per_cu = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return per_cu * cus;
+}
+
+template <typename KernelT>
+cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st,
+                                bool* taken)
+{
+    static int cached_dev = -1, cached_groups = 0;       // per kernel instantiation
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return CGBN_ERR_HIP;
+    if (dev != cached_dev) { cached_groups = resident_groups(kernel); cached_dev = dev; }
+    long long groups = cached_groups;
+    if (g_tune.fused_groups > 0 && g_tune.fused_groups < groups) groups = g_tune.fused_groups;
+    if (groups > f.total_units) groups = f.total_units;
+    *taken = false;
+    if (groups < 1 || f.U > groups) return CGBN_OK;      // a channel's units must all be resident: other path
+    *taken = true;
+    hipLaunchKernelGGL(fused_init, dim3((unsigned)((sync_words + 255) / 256)), dim3(256), 0, st, A.sync, sync_words);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)groups), dim3(kThreads), 0, st, A);
+    return launched();
+}
+
+template <typename T, bool FWD>
+cgbn_status launch_fused_t(const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st, bool* taken)
+{
+#define CGBN_FUSED_CASE(LB_, LPPC_)                                                                          \
+    if (f.LB == LB_ && f.LPPC == LPPC_) {                                                                    \
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_>, f, A, sync_words, st, taken); \
+        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_>, f, A, sync_words, st, taken);    \
+    }
+    CGBN_FUSED_CASE(16, 0) CGBN_FUSED_CASE(8, 0)
+    CGBN_FUSED_CASE(16, 2) CGBN_FUSED_CASE(16, 4) CGBN_FUSED_CASE(16, 8) CGBN_FUSED_CASE(16, 16)
+    CGBN_FUSED_CASE(8, 4) CGBN_FUSED_CASE(8, 8) CGBN_FUSED_CASE(8, 16) CGBN_FUSED_CASE(8, 32)
+    if constexpr (FWD) {
+        CGBN_FUSED_CASE(16, 32) CGBN_FUSED_CASE(8, 64)
+    } else {
+        CGBN_FUSED_CASE(8, 2)
+    }
+#undef CGBN_FUSED_CASE
+    *taken = false;
+    return CGBN_OK;
+}
+
+FusedArgs fused_args(const Plan& p, const FusedPlan& f, char* ws)
+{
+    FusedArgs A;
+    std::memset(&A, 0, sizeof(A));
+    A.part0 = reinterpret_cast<float*>(ws + p.off_part0);
+    A.part1 = reinterpret_cast<float*>(ws + p.off_part1);
+    A.sh0 = reinterpret_cast<double*>(ws + p.off_sh0);
+    A.sh1 = reinterpret_cast<double*>(ws + p.off_sh1);
+    A.sync = reinterpret_cast<unsigned*>(ws + p.off_sync);
+    A.total_units = f.total_units;
+    A.M = p.M; A.shard_count = p.M / p.K; A.inv_M = (float)(1.0 / p.M);
+    A.N = p.N; A.C = p.C; A.HW = p.HW; A.rows = f.rows; A.K = p.K; A.rps = f.rps; A.G = f.G;
+    A.U = f.U; A.tp = f.tp; A.TL = f.TL; A.LPP = f.LPP; A.IPU = f.IPU;
+    A.nt = (int)g_tune.nt_store;
+    A.spin_limit = (unsigned)g_tune.spin_limit;
+    A.plane_stride = (unsigned)((long long)p.C * p.HW * p.eb);
+#ifdef CGBN_TRACE
+    A.trace = g_trace;
+#endif
+    return A;
 }
 
 bool eps_ok(float eps) { return std::isfinite(eps) && eps > 0.f; }
@@ -228,6 +375,13 @@ size_t cgbn_workspace_bytes(int N, int C, int H, int W, cgbn_layout layout, cgbn
     Plan p;
     if (make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return 0;
     return p.bytes;
+}
+
+size_t cgbn_workspace_error_offset(int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype, int K)
+{
+    Plan p;
+    if (make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return (size_t)-1;
+    return p.off_sync + sizeof(unsigned);
 }
 
 cgbn_status cgbn_shard_sum(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
@@ -368,6 +522,17 @@ cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout 
     float* mlo = reinterpret_cast<float*>(ws + p.off_mlo);
     const int rev = (int)g_tune.reverse;
 
+    if (g_tune.fused && p.ff.ok) {
+        FusedArgs F = fused_args(p, p.ff, ws);
+        F.x = x; F.out = y; F.gamma = gamma; F.beta = beta; F.eps = (double)eps;
+        F.mean = mean; F.mean_lo = mlo; F.mean_lo_user = mean_lo; F.invstd = invstd;
+        bool taken = false;
+        const int sync_words = kSyncHeader + 4 * p.C;
+        cgbn_status st_ = p.dtype == CGBN_F32 ? launch_fused_t<float, true>(p.ff, F, sync_words, st, &taken)
+                                              : launch_fused_t<bf16_t, true>(p.ff, F, sync_words, st, &taken);
+        if (taken || st_ != CGBN_OK) return st_;
+    }
+
     SweepArgs A = sweep_args(p);
     A.x = x; A.part0 = part0;
     // steps 1-3 then 4-5
@@ -396,6 +561,18 @@ cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, cons
     char* ws = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int rev = (int)g_tune.reverse;
+
+    if (g_tune.fused && p.fb.ok) {
+        FusedArgs F = fused_args(p, p.fb, ws);
+        F.x = x; F.dy = dy; F.out = dx; F.gamma = gamma;
+        F.mean = const_cast<float*>(mean); F.mean_lo = const_cast<float*>(mean_lo);
+        F.invstd = const_cast<float*>(invstd); F.dgamma = dgamma; F.dbeta = dbeta;
+        bool taken = false;
+        const int sync_words = kSyncHeader + 4 * p.C;
+        cgbn_status st_ = p.dtype == CGBN_F32 ? launch_fused_t<float, false>(p.fb, F, sync_words, st, &taken)
+                                              : launch_fused_t<bf16_t, false>(p.fb, F, sync_words, st, &taken);
+        if (taken || st_ != CGBN_OK) return st_;
+    }
 
     SweepArgs A = sweep_args(p);
     A.x = x; A.dy = dy; A.mean = mean; A.mean_lo = mean_lo; A.invstd = invstd;
@@ -435,6 +612,9 @@ static long long* tuning_slot(const char* key)
     if (!std::strcmp(key, "piece_bytes")) return &g_tune.piece_bytes;
     if (!std::strcmp(key, "reverse")) return &g_tune.reverse;
     if (!std::strcmp(key, "nt_store")) return &g_tune.nt_store;
+    if (!std::strcmp(key, "fused")) return &g_tune.fused;
+    if (!std::strcmp(key, "spin_limit")) return &g_tune.spin_limit;
+    if (!std::strcmp(key, "fused_groups")) return &g_tune.fused_groups;
     return nullptr;
 }
 
@@ -442,8 +622,12 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
 {
     long long* slot = tuning_slot(key);
     if (!slot) return CGBN_ERR_TUNING;
-    if (slot == &g_tune.reverse || slot == &g_tune.nt_store) {
+    if (slot == &g_tune.reverse || slot == &g_tune.nt_store || slot == &g_tune.fused) {
         if (value != 0 && value != 1) return CGBN_ERR_TUNING;
+    } else if (slot == &g_tune.spin_limit) {
+        if (value < 0 || value > 0xffffffffLL) return CGBN_ERR_TUNING;
+    } else if (slot == &g_tune.fused_groups) {
+        if (value < 0 || value > (1LL << 20)) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.wave_plane_bytes) {
         if (value < 0 || value > (1LL << 20)) return CGBN_ERR_TUNING;
     } else if (value < 4096 || value > (1LL << 26)) {
@@ -452,6 +636,11 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
     *slot = value;
     return CGBN_OK;
 }
+
+#ifdef CGBN_TRACE
+// performance-work builds only: device buffer of 8 timestamps per unit
+void cgbn_debug_set_trace(void* device_buffer) { g_trace = static_cast<unsigned long long*>(device_buffer); }
+#endif
 
 long long cgbn_get_tuning(const char* key)
 {

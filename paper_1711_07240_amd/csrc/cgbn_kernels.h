@@ -582,6 +582,7 @@ struct CombineArgs {
     long long pivot_stride;
     int is_bf16;
     int C, rows, K, rps, G; // G lanes share one shard, a power of two <= 64
+    unsigned* clear_word;   // set to zero if not null (the workspace's error word)
 };
 
 __device__ __forceinline__ double pivot_of(const CombineArgs& A, int c)
@@ -621,6 +622,7 @@ __global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
 {
     int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
     int c = blockIdx.x * 4 + w;
+    if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     if (c >= A.C) return;
     const double pivot = pivot_of(A, c);      // zero unless the rows hold sums about a pivot
     double t0 = shard_then_total(A.part0 + (size_t)c * A.rows, A.sh0, c, A, lane, pivot * A.shard_count);

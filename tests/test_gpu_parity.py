@@ -14,6 +14,16 @@ from gpu_harness import DEV, Problem, check_against_oracle, widen, to_dev, to_ho
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True, params=[1, 0], ids=["fused", "sweeps"])
+def path(request):
+    """Every test runs twice: with the register-resident single-launch kernels
+    (where the shape allows them) and with the multi-sweep kernels only."""
+    old = L.cgbn_get_tuning("fused")
+    L.cgbn_set_tuning("fused", request.param)
+    yield request.param
+    L.cgbn_set_tuning("fused", old)
+
+
 def oracle_all(x, dy, gamma, beta, eps, layout, dtype):
     return O.cgbn_forward_backward_ref(widen(x, dtype), widen(dy, dtype), gamma.astype(np.float64),
                                        beta.astype(np.float64), eps, layout)
@@ -142,14 +152,14 @@ def test_step_entry_points_match_algorithm_1(layout, dtype):
     ref = dict(y=y_r, mean=mean_r, invstd=invstd_r, dx=dx_r, dgamma=dg_r, dbeta=db_r)
     check_against_oracle(got, ref, dtype, f"steps-{layout}-{dtype}")
 
-    # the fused entry points run the same sweeps; only the double-precision order of
-    # the reduce step differs, so the outputs agree to the last bit or two
+    # the fused entry points compute the same thing (with the same kernels, or with the
+    # register-resident ones): the outputs agree to float rounding
     q = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, layout, dtype, K)
     q.forward(); q.backward()
     got2 = q.results()
     for k in ("y", "mean", "invstd", "dx", "dgamma", "dbeta"):
         assert np.allclose(got[k], got2[k], rtol=1e-2 if dtype == "bf16" else 2e-6, atol=1e-6), k
-    assert np.allclose(got["mean"] + got["mean_lo"], got2["mean"] + got2["mean_lo"], rtol=1e-12, atol=1e-12)
+    assert np.allclose(got["mean"] + got["mean_lo"], got2["mean"] + got2["mean_lo"], rtol=2e-6, atol=2e-6)
 
 
 def test_shard_count_changes_only_rounding_and_runs_are_reproducible():
@@ -218,3 +228,40 @@ def test_mean_lo_matters_only_for_offset_data_and_null_is_accepted():
     r = p.results()
     assert np.max(np.abs(r["mean"] + r["mean_lo"] - ref["mean"])) < 1e-9
     check_against_oracle(r, ref, "f32", "offset with mean_lo")
+
+
+def test_bounded_wait_gives_up_cleanly(path):
+    """Failure handling of the single-launch kernels, forced from the host: with a
+    poll limit of zero a wait gives up unless its flag is already set.  The grid
+    must still drain, flag the error word and poison statistics with NaN rather
+    than return numbers computed from an incomplete reduction."""
+    if not path:
+        pytest.skip("the multi-sweep kernels have no device-side waits")
+    wl = BASE.scaled(N=8, C=64, H=96, W=128, K=4)
+    d = synth.make_inputs(wl)
+    p = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
+    off = L.cgbn_workspace_error_offset(wl.N, wl.C, wl.H, wl.W, wl.layout, wl.dtype, wl.K)
+    old = L.cgbn_get_tuning("spin_limit")
+    try:
+        L.cgbn_set_tuning("spin_limit", 0)
+        p.forward()
+        torch.cuda.synchronize()
+        gave_up = int(p.ws[off:off + 4].view(torch.int32).item())
+        r = p.results()
+    finally:
+        L.cgbn_set_tuning("spin_limit", old)
+    ref = oracle_all(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype)
+    assert gave_up in (0, 1)
+    any_nan = bool(np.isnan(r["y"]).any() or np.isnan(r["mean"]).any() or np.isnan(r["invstd"]).any())
+    assert any_nan == bool(gave_up)
+    # whatever is not NaN is right: never numbers from an incomplete reduction
+    for k in ("mean", "invstd", "y"):
+        fin = np.isfinite(r[k])
+        assert np.allclose(r[k][fin], ref[k][fin], rtol=1e-4, atol=1e-4), k
+    bad = ~np.isfinite(r["invstd"])
+    assert np.all(np.isnan(r["y"][:, bad]))
+    # and with the normal limit the same problem is clean
+    p.forward(); p.backward()
+    torch.cuda.synchronize()
+    assert int(p.ws[off:off + 4].view(torch.int32).item()) == 0
+    check_against_oracle(p.results(), ref, wl.dtype, "after the forced give-up")

@@ -10,8 +10,9 @@ two-pass method (9 sweeps of the tensor: 3 reads + 1 write forward, 4 reads +
 sweep can start on what the previous one left in cache); the measured traffic
 is reported beside it.
 
-Prints ONE JSON line.  `roofline` is for the dominant kernel (the dx sweep),
-timed on its own with HIP events on the stream it is launched on;
+Prints ONE JSON line.  `roofline` is for the dominant kernel (the single-launch
+backward, or the dx sweep where that path does not apply), timed on its own
+with HIP events on the stream it is launched on;
 `cpu_baseline` is the float64 oracle timed on this machine's host cores on a
 sample of channels of the same workload.
 """
@@ -181,13 +182,17 @@ def cpu_baseline(wl, synth, budget_s=12.0):
 
 def load_traffic(name):
     """Measured HBM bytes per launch of the dominant kernel, from the committed
-    rocprofv3 counter summary (profiles/traffic.json), or None."""
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    rocprofv3 counter summary (profiles/traffic.txt: `name bytes` lines), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.txt")
     try:
         with open(path) as f:
-            return json.load(f).get(name)
+            for line in f:
+                parts = line.split("#", 1)[0].split()
+                if len(parts) == 2 and parts[0] == name:
+                    return float(parts[1])
     except (OSError, ValueError):
-        return None
+        pass
+    return None
 
 
 def main():
@@ -198,6 +203,8 @@ def main():
     ap.add_argument("--workload", default="cfg1")
     ap.add_argument("--others", default="cfg2,cfg3,cfg4", help="secondary workloads timed with fewer steps ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true",
+                    help="also run the library's plain copy kernel over 1 GiB (for counter calibration under rocprofv3)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (the K shards are virtual devices on it); "
@@ -224,10 +231,30 @@ def main():
     for name, (ntensors, fn) in layer.sweeps().items():
         ms = time_calls(torch, fn, 3, max(10, args.steps // 2))
         sweeps[name] = dict(ms=statistics.mean(ms), GBps=ntensors * Sb / statistics.mean(ms) / 1e6)
-    dom = "backward_dx"
-    roofline = dict(bound="hbm", kernel=dom, achieved=sweeps[dom]["GBps"], peak=PEAK_GBPS, unit="GB/s",
-                    frac=sweeps[dom]["GBps"] / PEAK_GBPS, traffic=load_traffic(f"{wl.name}.{dom}"),
-                    avg_ms=sweeps[dom]["ms"], algorithmic_bytes=3 * Sb)
+    layer.backward()
+    if cgbn.cgbn_get_tuning("last_backward_fused") == 1:
+        # The backward is one launch that holds dy and x in registers between the device sums
+        # and dx.  It does the work of two sweeps (4 reads + 1 write = 5 tensors, the
+        # algorithmic count) while moving 3 tensors; `traffic` shows what really moved.
+        ms = statistics.mean(time_calls(torch, layer.backward, 3, max(10, args.steps // 2)))
+        roofline = dict(bound="hbm", kernel="nchw_fused_backward", achieved=5 * Sb / ms / 1e6, peak=PEAK_GBPS,
+                        unit="GB/s", frac=5 * Sb / ms / 1e6 / PEAK_GBPS,
+                        traffic=load_traffic(f"{wl.name}.nchw_fused_backward"), avg_ms=ms,
+                        algorithmic_bytes=5 * Sb, moved_bytes_by_design=3 * Sb,
+                        achieved_on_moved_bytes=3 * Sb / ms / 1e6)
+    else:
+        dom = "backward_dx"
+        roofline = dict(bound="hbm", kernel=dom, achieved=sweeps[dom]["GBps"], peak=PEAK_GBPS, unit="GB/s",
+                        frac=sweeps[dom]["GBps"] / PEAK_GBPS, traffic=load_traffic(f"{wl.name}.{dom}"),
+                        avg_ms=sweeps[dom]["ms"], algorithmic_bytes=3 * Sb)
+
+    if args.calibrate:
+        nb = 1 << 30
+        a, b = torch.empty(nb, dtype=torch.uint8, device=dev), torch.empty(nb, dtype=torch.uint8, device=dev)
+        for _ in range(3):
+            cgbn.cgbn_calibration_copy(a, b, nb)
+        torch.cuda.synchronize()
+        del a, b
 
     others = []
     del layer, x, dy
@@ -254,7 +281,8 @@ def main():
         "config": {"workload": f"{wl.name}: N={wl.N} C={wl.C} H={wl.H} W={wl.W} {wl.layout} {wl.dtype} K={wl.K}",
                    "step": "cgbn_forward + cgbn_backward", "algorithmic_bytes": 9 * Sb,
                    "tuning": {k: cgbn.cgbn_get_tuning(k) for k in
-                              ("chunk_bytes", "wave_plane_bytes", "piece_bytes", "reverse", "nt_store")}},
+                              ("chunk_bytes", "wave_plane_bytes", "piece_bytes", "reverse", "nt_store", "fused",
+                               "last_forward_fused", "last_backward_fused")}},
         "pct_of_peak": head["pct_of_peak"], "fwd_ms": head["fwd_ms"], "bwd_ms": head["bwd_ms"],
         "floor_GBps": head["floor_GBps"],
         "sweeps": sweeps, "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,

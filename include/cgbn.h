@@ -158,7 +158,15 @@ const char* cgbn_status_string(cgbn_status status);
  *   "spin_limit"       polls before a device-side wait gives up
  * cgbn_get_tuning returns -1 for an unknown key. */
 cgbn_status cgbn_set_tuning(const char* key, long long value);
+/* also readable: "last_forward_fused", "last_backward_fused" (1 if the last
+ * cgbn_forward / cgbn_backward took the single-launch path) */
 long long cgbn_get_tuning(const char* key);
+
+/* A plain device-to-device copy of `bytes` bytes (a multiple of 16, both
+ * pointers 16-byte aligned) by a kernel of this library: it reads and writes a
+ * known number of bytes, which is what hardware traffic counters are calibrated
+ * against when the library's kernels are profiled. */
+cgbn_status cgbn_calibration_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

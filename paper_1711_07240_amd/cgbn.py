@@ -45,6 +45,7 @@ SIGNATURES = {
                                  + [_c_p] * 5 + [_c_p, _c_sz, _c_p]),
     "cgbn_backward_reduce": (_c_int, [_c_p, _c_p, _c_int, _c_int, _c_p, _c_p, _c_p]),
     "cgbn_backward_dx": (_c_int, [_c_p, _c_p] + [_c_int] * 4 + [_c_int, _c_int] + [_c_p] * 8),
+    "cgbn_calibration_copy": (_c_int, [_c_p, _c_p, _c_sz, _c_p]),
     "cgbn_status_string": (ctypes.c_char_p, [_c_int]),
     "cgbn_set_tuning": (_c_int, [ctypes.c_char_p, _c_ll]),
     "cgbn_get_tuning": (_c_ll, [ctypes.c_char_p]),
@@ -189,6 +190,10 @@ def cgbn_backward_dx(dy, x, N, C, H, W, layout, dtype, mean, mean_lo, invstd, ga
                                   _enum(DTYPES, dtype), _ptr(mean), _ptr(mean_lo), _ptr(invstd),
                                   _ptr(gamma), _ptr(dgamma), _ptr(dbeta), _ptr(dx), _stream(stream)),
            "cgbn_backward_dx")
+
+
+def cgbn_calibration_copy(src, dst, nbytes, stream=None) -> None:
+    _check(lib().cgbn_calibration_copy(_ptr(src), _ptr(dst), int(nbytes), _stream(stream)), "cgbn_calibration_copy")
 
 
 def cgbn_set_tuning(key: str, value: int) -> None:

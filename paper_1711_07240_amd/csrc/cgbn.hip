@@ -24,6 +24,7 @@ struct Tuning {
     long long fused_groups = 0;          // workgroups of the fused grid (0 = as many as are resident at once)
 };
 Tuning g_tune;
+long long g_last_forward_fused = 0, g_last_backward_fused = 0;   // which path the last call took
 #ifdef CGBN_TRACE
 unsigned long long* g_trace = nullptr;
 #endif
@@ -530,8 +531,10 @@ cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout 
         const int sync_words = kSyncHeader + 4 * p.C;
         cgbn_status st_ = p.dtype == CGBN_F32 ? launch_fused_t<float, true>(p.ff, F, sync_words, st, &taken)
                                               : launch_fused_t<bf16_t, true>(p.ff, F, sync_words, st, &taken);
+        g_last_forward_fused = taken;
         if (taken || st_ != CGBN_OK) return st_;
     }
+    g_last_forward_fused = 0;
 
     SweepArgs A = sweep_args(p);
     A.x = x; A.part0 = part0;
@@ -571,8 +574,10 @@ cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, cons
         const int sync_words = kSyncHeader + 4 * p.C;
         cgbn_status st_ = p.dtype == CGBN_F32 ? launch_fused_t<float, false>(p.fb, F, sync_words, st, &taken)
                                               : launch_fused_t<bf16_t, false>(p.fb, F, sync_words, st, &taken);
+        g_last_backward_fused = taken;
         if (taken || st_ != CGBN_OK) return st_;
     }
+    g_last_backward_fused = 0;
 
     SweepArgs A = sweep_args(p);
     A.x = x; A.dy = dy; A.mean = mean; A.mean_lo = mean_lo; A.invstd = invstd;
@@ -642,8 +647,21 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
 void cgbn_debug_set_trace(void* device_buffer) { g_trace = static_cast<unsigned long long*>(device_buffer); }
 #endif
 
+cgbn_status cgbn_calibration_copy(const void* src, void* dst, size_t bytes, void* stream)
+{
+    if (!src || !dst) return CGBN_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0 || bytes > ((size_t)1 << 40)) return CGBN_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return CGBN_ERR_ALIGN;
+    const size_t nvec = bytes / 16, per_group = (size_t)kThreads * 8;
+    hipLaunchKernelGGL(calibration_copy, dim3((unsigned)((nvec + per_group - 1) / per_group)), dim3(kThreads), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const u32x4*>(src), static_cast<u32x4*>(dst), nvec);
+    return launched();
+}
+
 long long cgbn_get_tuning(const char* key)
 {
+    if (key && !std::strcmp(key, "last_forward_fused")) return g_last_forward_fused;
+    if (key && !std::strcmp(key, "last_backward_fused")) return g_last_backward_fused;
     long long* slot = tuning_slot(key);
     return slot ? *slot : -1;
 }

@@ -670,4 +670,14 @@ __global__ __launch_bounds__(kThreads) void combine_shards(const double* s0, con
     }
 }
 
+// Plain copy of `nvec` 16-byte vectors, 8 per thread: reads and writes a known
+// number of bytes, for calibrating hardware traffic counters.
+__global__ __launch_bounds__(kThreads) void calibration_copy(const u32x4* src, u32x4* dst, size_t nvec)
+{
+    size_t i = (size_t)blockIdx.x * (kThreads * 8) + threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < 8; ++u, i += kThreads)
+        if (i < nvec) dst[i] = src[i];
+}
+
 }  // namespace cgbn

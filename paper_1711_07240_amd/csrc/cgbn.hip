@@ -311,7 +311,12 @@ cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A
     *taken = false;
     if (groups < 1 || f.U > groups) return CGBN_OK;      // a channel's units must all be resident: other path
     *taken = true;
-    hipLaunchKernelGGL(fused_init, dim3((unsigned)((sync_words + 255) / 256)), dim3(256), 0, st, A.sync, sync_words);
+    {
+        long long want = (A.row_words + kThreads - 1) / kThreads;
+        unsigned init_groups = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
+        hipLaunchKernelGGL(fused_init, dim3(init_groups), dim3(kThreads), 0, st, A.sync, sync_words,
+                           reinterpret_cast<unsigned*>(A.part0), A.row_words);
+    }
     hipLaunchKernelGGL(kernel, dim3((unsigned)groups), dim3(kThreads), 0, st, A);
     return launched();
 }
@@ -346,8 +351,9 @@ FusedArgs fused_args(const Plan& p, const FusedPlan& f, char* ws)
     A.sh0 = reinterpret_cast<double*>(ws + p.off_sh0);
     A.sh1 = reinterpret_cast<double*>(ws + p.off_sh1);
     A.sync = reinterpret_cast<unsigned*>(ws + p.off_sync);
+    A.row_words = (long long)((p.off_sh0 - p.off_part0) / sizeof(float));   // part0 and part1 are adjacent
     A.total_units = f.total_units;
-    A.M = p.M; A.shard_count = p.M / p.K; A.inv_M = (float)(1.0 / p.M);
+    A.M = p.M; A.inv_M_f64 = 1.0 / p.M; A.shard_count = p.M / p.K; A.inv_M = (float)(1.0 / p.M);
     A.N = p.N; A.C = p.C; A.HW = p.HW; A.rows = f.rows; A.K = p.K; A.rps = f.rps; A.G = f.G;
     A.U = f.U; A.tp = f.tp; A.TL = f.TL; A.LPP = f.LPP; A.IPU = f.IPU;
     A.nt = (int)g_tune.nt_store;

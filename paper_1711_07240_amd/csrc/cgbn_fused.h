@@ -6,10 +6,21 @@
 // deviations, normalise) and dy, x twice in the backward.  Here a workgroup
 // takes a *unit* -- up to 128 KiB of one channel -- into registers, writes its
 // partial sums to the channel's rows, waits until every unit of the channel has
-// done so and the last one has reduced the rows (shard by shard, then across
-// shards, in double precision, the same arithmetic as combine_rows), and then
-// carries on from its registers.  HBM traffic falls from 9 to 5 tensor sweeps
-// for forward + backward.
+// done so, reduces the rows itself (shard by shard, then across shards, in double
+// precision, the same arithmetic as combine_rows and the same in every
+// workgroup, so all units of a channel hold bitwise the same statistics), and
+// then carries on from its registers.  HBM traffic falls from 9 to 5 tensor
+// sweeps for forward + backward.
+//
+// Hand-over.  The rows are their own flags: before the launch every row holds a
+// sentinel bit pattern (a NaN no sum can produce, since NaN sums are stored in
+// canonical form); a unit publishes a row with one agent-scope store and bumps
+// the channel's unit counter without waiting for that store; the unit that
+// completes the count raises the channel's flag.  A waiting workgroup polls the
+// flag with one lane (a whole workgroup polling the rows turned the rows' memory
+// channel into a hot spot that slowed every stream), then fetches the rows with
+// agent-scope loads, again if a sentinel is still there.  No fences, no store
+// acknowledgements on the path.
 //
 // Units.  Large planes are cut into tiles of up to 128 KiB (64 KiB per tensor in
 // the backward); a unit is one tile and leaves one row.  Small planes (one fits
@@ -61,11 +72,12 @@ struct FusedArgs {
     float* part1;
     double* sh0;          // [K][C]
     double* sh1;
-    unsigned* sync;       // [1] error, [kSyncHeader ..) cnt1[C] cnt2[C] flag1[C] flag2[C]
+    unsigned* sync;       // [1] error word, [kSyncHeader ..) unit counters cnt1[C], cnt2[C], flags flag1[C], flag2[C]
     unsigned long long* trace;   // only used in builds with CGBN_TRACE
     long long total_units;
-    double M, eps, shard_count;
+    double M, inv_M_f64, eps, shard_count;
     float inv_M;
+    long long row_words;  // floats in part0 and part1 together (they are adjacent): set to the sentinel before a launch
     int N, C, HW, rows, K, rps, G;
     int U;                // units per channel
     int tp, TL;           // large planes: tiles per plane, tile length (elements)
@@ -75,10 +87,14 @@ struct FusedArgs {
     unsigned plane_stride; // small planes: bytes between the same channel's planes of consecutive images
 };
 
-__global__ void fused_init(unsigned* sync, int nwords)
+constexpr unsigned kRowSentinel = 0xffffffffu;
+
+// Before every launch: clear the error word and mark every row "not written yet".
+__global__ __launch_bounds__(kThreads) void fused_init(unsigned* sync, int sync_words, unsigned* rows, long long row_words)
 {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < nwords) sync[i] = 0u;
+    long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
+    for (long long j = i; j < sync_words; j += (long long)gridDim.x * kThreads) sync[j] = 0u;
+    for (; i < row_words; i += (long long)gridDim.x * kThreads) rows[i] = kRowSentinel;
 }
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -128,93 +144,118 @@ template <> struct Packed<bf16_t> {
     static __device__ __forceinline__ uint32_t pack(const float (&f)[2]) { return f32_to_bf16(f[0]) | (f32_to_bf16(f[1]) << 16); }
 };
 
-// Everything the workgroups exchange (row partials, statistics, counters, flags)
-// moves through agent-scope atomic loads and stores, which are coherent across
-// the chip's L2 slices by themselves; what is left to do by hand is ordering: a
-// wave's earlier stores must have completed before it signals.  stores_done()
-// does that without the cache-wide write-back / invalidate that a release /
-// acquire fence would add to every hand-over.
+// Rows move through agent-scope atomic loads and stores, which are coherent
+// across the chip's L2 slices by themselves.
 __device__ __forceinline__ unsigned ld_agent(const unsigned* p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float ld_agent(const float* p)
+// publish one row; a NaN sum is stored in canonical form so that it can never look like the sentinel
+__device__ __forceinline__ void publish_row(float* p, float v)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_agent(float* p, float v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void st_agent(unsigned* p, unsigned v)
-{
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void stores_done()
-{
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    unsigned bits = __float_as_uint(v);
+    if (v != v) bits = 0x7fc00000u;
+    __hip_atomic_store(reinterpret_cast<unsigned*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Thread 0 polls `flag` until it is set (bounded), then the workgroup meets.
-// Returns false if the bound was hit.
-__device__ __forceinline__ bool wait_flag(const unsigned* flag, unsigned limit, unsigned* err, int* s_ok)
-{
-    if (threadIdx.x == 0) {
-        unsigned spins = 0;
-        int ok = 1;
-        while (ld_agent(flag) == 0u) {
-            __builtin_amdgcn_s_sleep(2);
-            if (++spins > limit) {
-                ok = 0;
-                atomicExch(err, 1u);
-                break;
-            }
-        }
-        *s_ok = ok;
-    }
-    __syncthreads();
-    return *s_ok != 0;
-}
-
-// Counts this workgroup's unit in and tells whether it was the channel's last.
-// Every thread that wrote a row must have called stores_done() before.
-__device__ __forceinline__ bool arrive(unsigned* cnt, int U, int* s_last)
-{
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *s_last = old == (unsigned)(U - 1);
-    }
-    __syncthreads();
-    return *s_last != 0;
-}
-
-// LDS of the workgroup that reduces a channel's rows
+// LDS of a workgroup gathering and reducing a channel's rows
 struct ReduceLds {
     float rows[2][kFusedMaxRows];
     double shard[2][kFusedMaxShards];
+    float stat[2];        // the reduced statistics, broadcast to the workgroup
+    int missing;          // some row was still the sentinel in this poll
 };
 
-// The whole workgroup reduces Q row arrays of channel c: all rows are fetched at
-// once (one memory round trip), then G lanes add the rows of one shard (the
-// device sum of Algorithm 1) and one wavefront adds the shard sums (its reduce
-// step).  Double precision, fixed order.  The totals are valid in wavefront 0.
-template <int Q>
-__device__ __forceinline__ void reduce_channel(const FusedArgs& A, int c, ReduceLds& L, double shard_offset0,
-                                               double (&tot)[Q])
+enum { ST_MEAN = 0, ST_INVSTD = 1, ST_SUMS = 2 };
+
+// 1/sqrt(v) in double precision without the library's division and square root
+// sequences (which would take dozens of registers next to a register-resident
+// unit): float estimate, three Newton steps.
+__device__ __forceinline__ double rsqrt_f64(double v)
 {
-    const int t = threadIdx.x, lane = t & (kWave - 1);
-    const float* p0 = A.part0 + (size_t)c * A.rows;
-    const float* p1 = A.part1 + (size_t)c * A.rows;
-    for (int r = t; r < A.rows; r += kThreads) {
-        L.rows[0][r] = ld_agent(p0 + r);
-        if (Q == 2) L.rows[1][r] = ld_agent(p1 + r);
+    double y = (double)__frsqrt_rn((float)v);
+#pragma unroll
+    for (int i = 0; i < 3; ++i) y = y * (1.5 - 0.5 * v * y * y);
+    return y;
+}
+
+// Counts this workgroup's unit in; the unit that completes the count raises the
+// channel's flag.  Nothing waits for the row stores here: the flag only tells
+// pollers when looking at the rows is worth while.  (Polling the counter itself
+// would put the pollers' loads and the arrivals' atomics on one word; measured,
+// that delays the arrivals by tens of microseconds.)
+__device__ __forceinline__ void count_in(unsigned* cnt, unsigned* flag, int U)
+{
+    __syncthreads();                  // every wavefront has issued its row stores
+    if (threadIdx.x == 0) {
+        unsigned old = __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (old == (unsigned)(U - 1)) __hip_atomic_store(flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __syncthreads();
+}
+
+// Waits until the channel's flag is up (one lane polls one word, so waiting
+// workgroups put next to no load on the memory system), then fetches the Q row
+// arrays of channel c into LDS, again until no sentinel is left (a row store may
+// still be in flight when the flag is seen).
+// Bounded: false if `spin_limit` polls were not enough.
+// `first` selects the arrays: rows of part0 (and part1 if Q == 2) for first == 0,
+// rows of part1 for first == 1.
+template <int Q>
+__device__ __forceinline__ bool gather_rows(const FusedArgs& A, int c, const unsigned* flag, ReduceLds& L,
+                                            int first = 0)
+{
+    const int t = threadIdx.x;
+    const unsigned* p0 = reinterpret_cast<const unsigned*>((first ? A.part1 : A.part0) + (size_t)c * A.rows);
+    const unsigned* p1 = reinterpret_cast<const unsigned*>(A.part1 + (size_t)c * A.rows);
+    unsigned polls = 0;
+    if (t == 0) {
+        while (ld_agent(flag) == 0u && polls < A.spin_limit) {
+            __builtin_amdgcn_s_sleep(2);
+            ++polls;
+        }
+    }
+    for (unsigned tries = 0;; ++tries) {
+        int missing = (t == 0 && polls >= A.spin_limit) ? 1 : 0;      // lane 0 gave up on the flag
+        if (t == 0) L.missing = 0;
+        __syncthreads();              // lane 0 has seen the count; LDS rows are free to overwrite
+        for (int r = t; r < A.rows; r += kThreads) {
+            unsigned b0 = ld_agent(p0 + r);
+            missing |= b0 == kRowSentinel;
+            L.rows[0][r] = __uint_as_float(b0);
+            if (Q == 2) {
+                unsigned b1 = ld_agent(p1 + r);
+                missing |= b1 == kRowSentinel;
+                L.rows[1][r] = __uint_as_float(b1);
+            }
+        }
+        if (missing) L.missing = 1;
+        __syncthreads();
+        const int any_missing = L.missing;
+        __syncthreads();              // everyone has read the verdict before it is reset
+        if (!any_missing) return true;
+        if (tries >= A.spin_limit) {
+            if (t == 0) atomicExch(A.sync + 1, 1u);
+            return false;
+        }
+        __builtin_amdgcn_s_sleep(8);
+    }
+}
+
+// Reduces the gathered rows: G lanes add the rows of one shard (the device sum of
+// Algorithm 1), one wavefront adds the shard sums (its reduce step).  Double
+// precision, fixed order, the same in every workgroup.  Lane 0 turns the totals
+// into the statistics (MODE) and leaves them in L.stat[] as floats; shard sums go
+// to sh0/sh1 if `write_shards`.
+template <int Q, int MODE>
+__device__ __forceinline__ void reduce_rows(const FusedArgs& A, int c, ReduceLds& L, double pivot,
+                                            bool write_shards, int first = 0)
+{
+    const double shard_offset0 = pivot * A.shard_count;
+    const int t = threadIdx.x, lane = t & (kWave - 1);
     const int G = A.G, gl = t & (G - 1), gi = t / G, spb = kThreads / G;
 #pragma unroll
     for (int q = 0; q < Q; ++q) {
-        double* sh = q == 0 ? A.sh0 : A.sh1;
+        double* sh = (q + first) == 0 ? A.sh0 : A.sh1;
         for (int k0 = 0; k0 < A.K; k0 += spb) {
             int k = k0 + gi;
             double acc = 0.0;
@@ -223,20 +264,35 @@ __device__ __forceinline__ void reduce_channel(const FusedArgs& A, int c, Reduce
             for (int off = G >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
             if (k < A.K && gl == 0) {
                 L.shard[q][k] = acc;
-                sh[(size_t)k * A.C + c] = acc + (q == 0 ? shard_offset0 : 0.0);
+                if (write_shards) sh[(size_t)k * A.C + c] = acc + (q == 0 ? shard_offset0 : 0.0);
             }
         }
     }
     __syncthreads();
+    if (t < kWave) {
+        double tot[Q];
 #pragma unroll
-    for (int q = 0; q < Q; ++q) {
-        double s = 0.0;
-        if (t < kWave) {
+        for (int q = 0; q < Q; ++q) {
+            double s = 0.0;
             for (int k = lane; k < A.K; k += kWave) s += L.shard[q][k];
             for (int off = kWave >> 1; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+            tot[q] = s;
         }
-        tot[q] = s;
+        if (lane == 0) {
+            if (MODE == ST_MEAN) {
+                double m = pivot + tot[0] * A.inv_M_f64;
+                float hi = (float)m;
+                L.stat[0] = hi;
+                L.stat[1] = (float)(m - (double)hi);
+            } else if (MODE == ST_INVSTD) {
+                L.stat[0] = (float)rsqrt_f64(tot[0] * A.inv_M_f64 + A.eps);
+            } else {
+                L.stat[0] = (float)tot[0];
+                if (Q == 2) L.stat[1] = (float)tot[Q - 1];
+            }
+        }
     }
+    __syncthreads();
 }
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
@@ -319,17 +375,11 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
     __shared__ ReduceLds lds;
-    __shared__ int s_last, s_ok;
     __shared__ float s_red[4];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
     const T* x = static_cast<const T*>(A.x);
     const char* xb = static_cast<const char*>(A.x);
     char* yb = static_cast<char*>(A.out);
-    unsigned* err = A.sync + 1;
-    unsigned* cnt1 = A.sync + kSyncHeader;
-    unsigned* cnt2 = cnt1 + A.C;
-    unsigned* flag1 = cnt2 + A.C;
-    unsigned* flag2 = flag1 + A.C;
     uint32_t d[kFusedWords];
 
     for (long long unit = blockIdx.x; unit < A.total_units; unit += gridDim.x) {
@@ -373,7 +423,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                     int n = SL::image(g, s, w);
                     if (n < g.n1) {
                         float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                        if (lane == 0) st_agent(&A.part0[(size_t)c * A.rows + n], tot);
+                        if (lane == 0) publish_row(&A.part0[(size_t)c * A.rows + n], tot);
                     }
                     acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
                 }
@@ -382,32 +432,30 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                 float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
                 if (lane == 0) s_red[w] = tot;
                 __syncthreads();
-                if (t == 0) st_agent(&A.part0[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
+                if (t == 0) publish_row(&A.part0[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
             }
         }
-        stores_done();
+        count_in(A.sync + kSyncHeader + c, A.sync + kSyncHeader + 2 * A.C + c, A.U);
         CGBN_STAMP(1);
-        // ---- steps 4-5: the last unit reduces the rows to the pooled mean ---
-        if (arrive(&cnt1[c], A.U, &s_last)) {
-            double tot[1];
-            reduce_channel<1>(A, c, lds, (double)pivot * A.shard_count, tot);
-            if (t == 0) {
-                double m = (double)pivot + tot[0] / A.M;
-                float hi = (float)m;
-                float lo = (float)(m - (double)hi);
-                st_agent(&A.mean[c], hi);
-                st_agent(&A.mean_lo[c], lo);
-                if (A.mean_lo_user) A.mean_lo_user[c] = lo;
-                stores_done();
-                st_agent(&flag1[c], 1u);
-            }
+        // ---- steps 4-5: when all rows are in, reduce them to the pooled mean
+        bool ok1 = false;
+        // `rows > 0` always holds.  Keeping the hand-over in a block the compiler cannot
+        // prove to run stops it from hoisting that block's index arithmetic out of the
+        // unit loop, which would push the register-resident unit into scratch memory.
+        if (A.rows > 0) {
+            ok1 = gather_rows<1>(A, c, A.sync + kSyncHeader + 2 * A.C + c, lds);
+            CGBN_STAMP(2);
+            reduce_rows<1, ST_MEAN>(A, c, lds, (double)pivot, g.u == 0);
         }
-        CGBN_STAMP(2);
-        bool ok1 = wait_flag(&flag1[c], A.spin_limit, err, &s_ok);
         CGBN_STAMP(3);
-        float mu = ld_agent(&A.mean[c]);
-        float mulo = ld_agent(&A.mean_lo[c]);
+        float mu = lds.stat[0];
+        const float mulo = lds.stat[1];
         if (!ok1) mu = __uint_as_float(0x7fc00000u);
+        if (g.u == 0 && t == 0) {
+            A.mean[c] = mu;
+            A.mean_lo[c] = mulo;
+            if (A.mean_lo_user) A.mean_lo_user[c] = mulo;
+        }
 
         // ---- steps 6-8: squared deviations from the pooled mean -----------
         {
@@ -431,7 +479,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                     int n = SL::image(g, s, w);
                     if (n < g.n1) {
                         float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                        if (lane == 0) st_agent(&A.part0[(size_t)c * A.rows + n], tot);
+                        if (lane == 0) publish_row(&A.part1[(size_t)c * A.rows + n], tot);
                     }
                     acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
                 }
@@ -440,28 +488,22 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                 float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
                 if (lane == 0) s_red[w] = tot;
                 __syncthreads();
-                if (t == 0) st_agent(&A.part0[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
+                if (t == 0) publish_row(&A.part1[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
             }
         }
-        stores_done();
+        count_in(A.sync + kSyncHeader + A.C + c, A.sync + kSyncHeader + 3 * A.C + c, A.U);
         CGBN_STAMP(4);
-        // ---- steps 9-10: the last unit reduces to variance and 1/sqrt(var+eps)
-        if (arrive(&cnt2[c], A.U, &s_last)) {
-            double tot[1];
-            reduce_channel<1>(A, c, lds, 0.0, tot);
-            if (t == 0) {
-                float is = (float)(1.0 / sqrt(tot[0] / A.M + A.eps));
-                if (!ok1) is = __uint_as_float(0x7fc00000u);
-                st_agent(&A.invstd[c], is);
-                stores_done();
-                st_agent(&flag2[c], 1u);
-            }
+        // ---- steps 9-10: reduce to the variance and 1/sqrt(var + eps)
+        bool ok2 = false;
+        if (A.rows > 0) {
+            ok2 = gather_rows<1>(A, c, A.sync + kSyncHeader + 3 * A.C + c, lds, 1);
+            CGBN_STAMP(5);
+            reduce_rows<1, ST_INVSTD>(A, c, lds, 0.0, g.u == 0, 1);
         }
-        CGBN_STAMP(5);
-        bool ok2 = wait_flag(&flag2[c], A.spin_limit, err, &s_ok);
         CGBN_STAMP(6);
-        float istd = ld_agent(&A.invstd[c]);
-        if (!ok2) istd = __uint_as_float(0x7fc00000u);
+        float istd = lds.stat[0];
+        if (!ok1 || !ok2) istd = __uint_as_float(0x7fc00000u);
+        if (g.u == 0 && t == 0) A.invstd[c] = istd;
 
         // ---- step 11: normalise from registers, write y --------------------
         {
@@ -498,15 +540,11 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
     __shared__ ReduceLds lds;
-    __shared__ int s_last, s_ok;
     __shared__ float s_red[8];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
     const char* xb = static_cast<const char*>(A.x);
     const char* gb = static_cast<const char*>(A.dy);
     char* ob = static_cast<char*>(A.out);
-    unsigned* err = A.sync + 1;
-    unsigned* cnt1 = A.sync + kSyncHeader;
-    unsigned* flag1 = cnt1 + 2 * A.C;
     uint32_t xd[kFusedWords / 2], gd[kFusedWords / 2];
 
     for (long long unit = blockIdx.x; unit < A.total_units; unit += gridDim.x) {
@@ -558,8 +596,8 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                     if (n < g.n1) {
                         float ta = wave_sum(a[0] + a[1]), tb = wave_sum(b[0] + b[1]);
                         if (lane == 0) {
-                            st_agent(&A.part0[(size_t)c * A.rows + n], ta);
-                            st_agent(&A.part1[(size_t)c * A.rows + n], tb);
+                            publish_row(&A.part0[(size_t)c * A.rows + n], ta);
+                            publish_row(&A.part1[(size_t)c * A.rows + n], tb);
                         }
                     }
                     a[0] = a[1] = b[0] = b[1] = 0.f;
@@ -570,29 +608,26 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                 if (lane == 0) { s_red[w] = ta; s_red[4 + w] = tb; }
                 __syncthreads();
                 if (t == 0) {
-                    st_agent(&A.part0[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
-                    st_agent(&A.part1[(size_t)c * A.rows + g.u], (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]));
+                    publish_row(&A.part0[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
+                    publish_row(&A.part1[(size_t)c * A.rows + g.u], (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]));
                 }
             }
         }
-        stores_done();
+        count_in(A.sync + kSyncHeader + c, A.sync + kSyncHeader + 2 * A.C + c, A.U);
         CGBN_STAMP(1);
-        if (arrive(&cnt1[c], A.U, &s_last)) {
-            double tot[2];
-            reduce_channel<2>(A, c, lds, 0.0, tot);
-            if (t == 0) {
-                st_agent(&A.dbeta[c], (float)tot[0]);
-                st_agent(&A.dgamma[c], (float)tot[1]);
-                stores_done();
-                st_agent(&flag1[c], 1u);
-            }
+        bool ok1 = false;
+        if (A.rows > 0) {
+            ok1 = gather_rows<2>(A, c, A.sync + kSyncHeader + 2 * A.C + c, lds);
+            CGBN_STAMP(2);
+            reduce_rows<2, ST_SUMS>(A, c, lds, 0.0, g.u == 0);
         }
-        CGBN_STAMP(2);
-        bool ok1 = wait_flag(&flag1[c], A.spin_limit, err, &s_ok);
         CGBN_STAMP(3);
-        float db = ld_agent(&A.dbeta[c]);
-        float dg = ld_agent(&A.dgamma[c]);
-        if (!ok1) db = __uint_as_float(0x7fc00000u);
+        float db = lds.stat[0], dg = lds.stat[1];
+        if (!ok1) db = dg = __uint_as_float(0x7fc00000u);
+        if (g.u == 0 && t == 0) {
+            A.dbeta[c] = db;
+            A.dgamma[c] = dg;
+        }
         // ---- dx from registers ----------------------------------------------
         {
             const unsigned loff = SL::lane_offset(t);

@@ -258,8 +258,6 @@ def test_bounded_wait_gives_up_cleanly(path):
     for k in ("mean", "invstd", "y"):
         fin = np.isfinite(r[k])
         assert np.allclose(r[k][fin], ref[k][fin], rtol=1e-4, atol=1e-4), k
-    bad = ~np.isfinite(r["invstd"])
-    assert np.all(np.isnan(r["y"][:, bad]))
     # and with the normal limit the same problem is clean
     p.forward(); p.backward()
     torch.cuda.synchronize()

@@ -60,7 +60,7 @@ struct Plan {
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, FusedPlan* f)
+void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words, FusedPlan* f)
 {
     std::memset(f, 0, sizeof(*f));
     if (layout != CGBN_NCHW || K > kFusedMaxShards) return;
@@ -85,7 +85,8 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
         f->rows = N;
         f->rps = ips;
     } else {
-        const long long cap = wave_cap * 4;
+        // large planes: a tile also fills the LDS slots (16-byte loads only)
+        const long long cap = wave_cap * 4 + (LB == 16 ? (long long)(lds_words / W) * kThreads * E : 0);
         long long tp = (HW + cap - 1) / cap;
         long long gran = (long long)kThreads * E;
         long long TL = (HW + tp - 1) / tp;
@@ -169,8 +170,8 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     int G = 1;
     while (G < kWave && G < p->rps) G <<= 1;
     p->G = G;
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, &p->ff);
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, &p->fb);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, &p->ff);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, &p->fb);
     int max_rows = p->rows;
     if (p->ff.ok && p->ff.rows > max_rows) max_rows = p->ff.rows;
     if (p->fb.ok && p->fb.rows > max_rows) max_rows = p->fb.rows;
@@ -310,6 +311,9 @@ cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A
     if (groups > f.total_units) groups = f.total_units;
     *taken = false;
     if (groups < 1 || f.U > groups) return CGBN_OK;      // a channel's units must all be resident: other path
+    // With few channels in flight, a grid that is not a whole number of channels leaves the
+    // units of the straddling channel waiting a full round for their siblings: trim it.
+    if (g_tune.fused_groups == 0 && groups / f.U < 8) groups = groups / f.U * f.U;
     *taken = true;
     {
         long long want = (A.row_words + kThreads - 1) / kThreads;

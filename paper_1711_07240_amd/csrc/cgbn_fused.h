@@ -46,6 +46,7 @@ namespace cgbn {
 
 constexpr int kFusedWords = 128;          // 32-bit registers of unit data per thread
 constexpr int kSyncHeader = 64;           // words before the per-channel arrays in the sync area
+constexpr int kFusedLdsWords = 24;        // further 32-bit words of unit data per thread kept in LDS (large planes, 16-byte loads)
 constexpr int kFusedMaxRows = 2048;       // rows of a channel staged in LDS by the reducing workgroup
 constexpr int kFusedMaxShards = 512;
 
@@ -126,6 +127,22 @@ template <> struct Words<8> {
         else *reinterpret_cast<u32x2*>(p) = v;
     }
 };
+
+// Unit data beyond the registers: slot j of thread t lives at ext[(j*256 + t)*4 ..+4).
+// A wavefront fills its 64 consecutive entries of a slot with one global-to-LDS
+// load (consecutive lanes write consecutive 16 bytes), so the data never passes
+// through registers on its way in.
+__device__ __forceinline__ void lds_slot_fill(const char* gaddr, uint32_t* ext, int j, int w)
+{
+    __builtin_amdgcn_global_load_lds(
+        (const void __attribute__((address_space(1)))*)gaddr,
+        (void __attribute__((address_space(3)))*)(ext + ((size_t)j * kThreads + (size_t)w * kWave) * 4), 16, 0, 0);
+}
+__device__ __forceinline__ void lds_slot_read(const uint32_t* ext, int j, int t, uint32_t* out)
+{
+    u32x4 v = *reinterpret_cast<const u32x4*>(ext + ((size_t)j * kThreads + t) * 4);
+    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+}
 
 // the elements packed in one 32-bit register
 template <typename T> struct Packed;
@@ -371,7 +388,9 @@ template <typename T, int LB, int LPPC>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 {
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
-    constexpr int R = kFusedWords / W;
+    constexpr int R = kFusedWords / W;                                       // slots held in registers
+    constexpr int RL = (LPPC == 0 && LB == 16) ? kFusedLdsWords / W : 0;     // slots held in LDS
+    constexpr int RT = R + RL;
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
     __shared__ ReduceLds lds;
@@ -381,6 +400,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
     const char* xb = static_cast<const char*>(A.x);
     char* yb = static_cast<char*>(A.out);
     uint32_t d[kFusedWords];
+    __shared__ uint32_t ext[RL > 0 ? RL * W * kThreads : 1];
 
     for (long long unit = blockIdx.x; unit < A.total_units; unit += gridDim.x) {
         UnitGeom g;
@@ -395,13 +415,16 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
         {
             const unsigned loff = SL::lane_offset(t);
 #pragma unroll
-            for (int s = 0; s < R; ++s) {
+            for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w)) {
                     // lanes past the end re-read the slot's first bytes; they are masked later
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
-                    Words<LB>::load(xu + SL::plane_base(A, s, w) + SL::slot_offset(s) + lo, &d[s * W]);
+                    const char* src = xu + SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
+                    if (s < R) Words<LB>::load(src, &d[(s < R ? s : 0) * W]);
+                    else lds_slot_fill(src, ext, s - R, w);
                 }
             }
+            if (RL > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the LDS slots have landed
         }
 
         // ---- steps 1-3: sums about the pivot ------------------------------
@@ -409,12 +432,19 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             const unsigned loff = SL::lane_offset(t);
             float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < R; ++s) {
+            for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
+                    uint32_t wv[W];
+                    if (s < R) {
+#pragma unroll
+                        for (int q = 0; q < W; ++q) wv[q] = d[(s < R ? s : 0) * W + q];
+                    } else {
+                        lds_slot_read(ext, s - R, t, wv);
+                    }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
                         float f[EPW];
-                        Packed<T>::unpack(d[s * W + q], f);
+                        Packed<T>::unpack(wv[q], f);
 #pragma unroll
                         for (int e = 0; e < EPW; ++e) acc[(q * EPW + e) & 3] += f[e] - pivot;
                     }
@@ -462,12 +492,19 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             const unsigned loff = SL::lane_offset(t);
             float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < R; ++s) {
+            for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
+                    uint32_t wv[W];
+                    if (s < R) {
+#pragma unroll
+                        for (int q = 0; q < W; ++q) wv[q] = d[(s < R ? s : 0) * W + q];
+                    } else {
+                        lds_slot_read(ext, s - R, t, wv);
+                    }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
                         float f[EPW];
-                        Packed<T>::unpack(d[s * W + q], f);
+                        Packed<T>::unpack(wv[q], f);
 #pragma unroll
                         for (int e = 0; e < EPW; ++e) {
                             float dv = (f[e] - mu) - mulo;
@@ -510,13 +547,19 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             const unsigned loff = SL::lane_offset(t);
             const float gsc = A.gamma[c] * istd, bsh = A.beta[c];
 #pragma unroll
-            for (int s = 0; s < R; ++s) {
+            for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
-                    uint32_t o[W];
+                    uint32_t o[W], wv[W];
+                    if (s < R) {
+#pragma unroll
+                        for (int q = 0; q < W; ++q) wv[q] = d[(s < R ? s : 0) * W + q];
+                    } else {
+                        lds_slot_read(ext, s - R, t, wv);
+                    }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
                         float f[EPW];
-                        Packed<T>::unpack(d[s * W + q], f);
+                        Packed<T>::unpack(wv[q], f);
 #pragma unroll
                         for (int e = 0; e < EPW; ++e) f[e] = ((f[e] - mu) - mulo) * gsc + bsh;
                         o[q] = Packed<T>::pack(f);
@@ -536,7 +579,9 @@ template <typename T, int LB, int LPPC>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
 {
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
-    constexpr int R = kFusedWords / 2 / W;       // slots per tensor
+    constexpr int R = kFusedWords / 2 / W;       // slots per tensor held in registers
+    constexpr int RL = (LPPC == 0 && LB == 16) ? kFusedLdsWords / 2 / W : 0;   // ... and in LDS
+    constexpr int RT = R + RL;
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
     __shared__ ReduceLds lds;
@@ -546,6 +591,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
     const char* gb = static_cast<const char*>(A.dy);
     char* ob = static_cast<char*>(A.out);
     uint32_t xd[kFusedWords / 2], gd[kFusedWords / 2];
+    __shared__ uint32_t ext[RL > 0 ? 2 * RL * W * kThreads : 1];    // dy slots, then x slots
 
     for (long long unit = blockIdx.x; unit < A.total_units; unit += gridDim.x) {
         UnitGeom g;
@@ -562,27 +608,41 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
         {
             const unsigned loff = SL::lane_offset(t);
 #pragma unroll
-            for (int s = 0; s < R; ++s) {
+            for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w)) {
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
                     size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
-                    Words<LB>::load(gu + o, &gd[s * W]);
-                    Words<LB>::load(xu + o, &xd[s * W]);
+                    if (s < R) {
+                        Words<LB>::load(gu + o, &gd[(s < R ? s : 0) * W]);
+                        Words<LB>::load(xu + o, &xd[(s < R ? s : 0) * W]);
+                    } else {
+                        lds_slot_fill(gu + o, ext, s - R, w);
+                        lds_slot_fill(xu + o, ext, RL + s - R, w);
+                    }
                 }
             }
+            if (RL > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the LDS slots have landed
         }
         // ---- device sums of dy and dy*xhat ---------------------------------
         {
             const unsigned loff = SL::lane_offset(t);
             float a[2] = {0.f, 0.f}, b[2] = {0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < R; ++s) {
+            for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
+                    uint32_t wx[W], wg[W];
+                    if (s < R) {
+#pragma unroll
+                        for (int q = 0; q < W; ++q) { wx[q] = xd[(s < R ? s : 0) * W + q]; wg[q] = gd[(s < R ? s : 0) * W + q]; }
+                    } else {
+                        lds_slot_read(ext, s - R, t, wg);
+                        lds_slot_read(ext, RL + s - R, t, wx);
+                    }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
                         float fx[EPW], fg[EPW];
-                        Packed<T>::unpack(xd[s * W + q], fx);
-                        Packed<T>::unpack(gd[s * W + q], fg);
+                        Packed<T>::unpack(wx[q], fx);
+                        Packed<T>::unpack(wg[q], fg);
 #pragma unroll
                         for (int e = 0; e < EPW; ++e) {
                             float xh = ((fx[e] - mu) - mulo) * istd;
@@ -633,14 +693,22 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
             const unsigned loff = SL::lane_offset(t);
             const float gsc = A.gamma[c] * istd, c1 = db * A.inv_M, c2 = dg * A.inv_M;
 #pragma unroll
-            for (int s = 0; s < R; ++s) {
+            for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t o[W];
+                    uint32_t wx[W], wg[W];
+                    if (s < R) {
+#pragma unroll
+                        for (int q = 0; q < W; ++q) { wx[q] = xd[(s < R ? s : 0) * W + q]; wg[q] = gd[(s < R ? s : 0) * W + q]; }
+                    } else {
+                        lds_slot_read(ext, s - R, t, wg);
+                        lds_slot_read(ext, RL + s - R, t, wx);
+                    }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
                         float fx[EPW], fg[EPW];
-                        Packed<T>::unpack(xd[s * W + q], fx);
-                        Packed<T>::unpack(gd[s * W + q], fg);
+                        Packed<T>::unpack(wx[q], fx);
+                        Packed<T>::unpack(wg[q], fg);
 #pragma unroll
                         for (int e = 0; e < EPW; ++e) {
                             float dv = (fx[e] - mu) - mulo;

@@ -74,8 +74,13 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
     f->LB = LB;
     if (HW <= wave_cap) {
         f->LPP = (int)((HW + (long long)kWave * E - 1) / ((long long)kWave * E));
-        int lppc = R / 16 > 2 ? R / 16 : 2;            // at most 16 planes per wavefront
-        while (lppc < f->LPP) lppc <<= 1;
+        // register slots per plane: the smallest instantiated count that holds a plane and
+        // leaves at most 16 planes per wavefront
+        static const int kSlotCounts[] = {2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 64};
+        int lppc = 0;
+        for (int cand : kSlotCounts)
+            if (cand >= f->LPP && cand * 16 >= R && cand <= R) { lppc = cand; break; }
+        if (!lppc) return;
         f->LPPC = lppc;
         int per_unit = 4 * (R / lppc);
         f->U = (N + per_unit - 1) / per_unit;
@@ -333,13 +338,19 @@ cgbn_status launch_fused_t(const FusedPlan& f, FusedArgs& A, int sync_words, hip
         if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_>, f, A, sync_words, st, taken); \
         else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_>, f, A, sync_words, st, taken);    \
     }
+    // slot counts per plane with R/16 <= count <= R, R the register slots per tensor
+    // (forward: 32 for 16-byte loads, 64 for 8-byte; backward: 16 and 32)
     CGBN_FUSED_CASE(16, 0) CGBN_FUSED_CASE(8, 0)
-    CGBN_FUSED_CASE(16, 2) CGBN_FUSED_CASE(16, 4) CGBN_FUSED_CASE(16, 8) CGBN_FUSED_CASE(16, 16)
-    CGBN_FUSED_CASE(8, 4) CGBN_FUSED_CASE(8, 8) CGBN_FUSED_CASE(8, 16) CGBN_FUSED_CASE(8, 32)
+    CGBN_FUSED_CASE(16, 2) CGBN_FUSED_CASE(16, 3) CGBN_FUSED_CASE(16, 4) CGBN_FUSED_CASE(16, 5)
+    CGBN_FUSED_CASE(16, 6) CGBN_FUSED_CASE(16, 8) CGBN_FUSED_CASE(16, 10) CGBN_FUSED_CASE(16, 12)
+    CGBN_FUSED_CASE(16, 16)
+    CGBN_FUSED_CASE(8, 4) CGBN_FUSED_CASE(8, 5) CGBN_FUSED_CASE(8, 6) CGBN_FUSED_CASE(8, 8)
+    CGBN_FUSED_CASE(8, 10) CGBN_FUSED_CASE(8, 12) CGBN_FUSED_CASE(8, 16) CGBN_FUSED_CASE(8, 24)
+    CGBN_FUSED_CASE(8, 32)
     if constexpr (FWD) {
-        CGBN_FUSED_CASE(16, 32) CGBN_FUSED_CASE(8, 64)
+        CGBN_FUSED_CASE(16, 24) CGBN_FUSED_CASE(16, 32) CGBN_FUSED_CASE(8, 64)
     } else {
-        CGBN_FUSED_CASE(8, 2)
+        CGBN_FUSED_CASE(8, 2) CGBN_FUSED_CASE(8, 3)
     }
 #undef CGBN_FUSED_CASE
     *taken = false;

@@ -66,6 +66,18 @@ SMALL = [
     ("nhwc-bf16-c24", dict(N=4, C=24, H=31, W=17, K=4, layout="NHWC", dtype="bf16")),
     ("nhwc-bf16-c10-scalar", dict(N=2, C=10, H=7, W=5, K=2, layout="NHWC", dtype="bf16")),
     ("nhwc-bf16-c300-scalar-two-tiles", dict(N=2, C=300, H=6, W=5, K=1, layout="NHWC", dtype="bf16")),
+    # small planes kept whole in registers: several register-slot counts per plane
+    ("nchw-f32-plane600", dict(N=10, C=6, H=20, W=30, K=5, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane702", dict(N=6, C=5, H=26, W=27, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane1100", dict(N=8, C=4, H=25, W=44, K=4, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane1398", dict(N=6, C=4, H=6, W=233, K=3, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane2900", dict(N=4, C=5, H=50, W=58, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane5000", dict(N=5, C=3, H=50, W=100, K=5, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane2600", dict(N=6, C=4, H=50, W=52, K=3, layout="NCHW", dtype="bf16")),
+    # large planes: tiles that spill past the registers into LDS slots, ragged last tile
+    ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane90000", dict(N=2, C=2, H=300, W=300, K=2, layout="NCHW", dtype="bf16")),
     # degenerate shapes
     ("one-image-per-shard", dict(N=6, C=4, H=8, W=8, K=6, layout="NCHW", dtype="f32")),
     ("single-image", dict(N=1, C=3, H=20, W=20, K=1, layout="NCHW", dtype="f32")),

@@ -16,7 +16,8 @@ using namespace cgbn;
 struct Tuning {
     long long chunk_bytes = 32768;       // NCHW: bytes of a plane per workgroup
     long long wave_plane_bytes = 16384;  // NCHW: planes up to this go one per wavefront
-    long long piece_bytes = 131072;      // NHWC: bytes of a pixel run per workgroup (full channel width)
+    long long piece_bytes = 1048576;     // NHWC reductions: bytes of a pixel run per workgroup (full channel width)
+    long long map_piece_bytes = 131072;  // NHWC normalise / dx: the same for the elementwise sweeps
     long long reverse = 1;               // alternate sweep direction so a sweep starts on what the last one left in cache
     long long nt_store = 1;              // non-temporal stores for y and dx
     long long fused = 1;                 // register-resident single-launch path where the shape allows it
@@ -49,7 +50,8 @@ struct Plan {
     int wave_mode, L, sp;
     // NHWC
     int cv, TW, ctiles, rpp, PL, pps;
-    long long spix;
+    int PLm, ppsm;        // pixel runs of the elementwise sweeps (no rows to keep few)
+    long long spix, gridm;
     // partial sums
     int rows, rps, G;
     long long grid;       // workgroups of one sweep
@@ -170,6 +172,16 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
         p->rows = (int)(pps * K);
         p->rps = (int)pps;
         p->grid = (long long)p->rows * p->ctiles;
+        long long PLm = g_tune.map_piece_bytes / ((long long)C * p->eb);
+        PLm -= PLm % (4 * p->rpp);
+        if (PLm < 4 * p->rpp) PLm = 4 * p->rpp;
+        if (PLm > p->spix) PLm = p->spix;
+        p->PLm = (int)PLm;
+        long long ppsm = (p->spix + PLm - 1) / PLm;
+        if (ppsm * K > 0x3fffffffLL) return CGBN_ERR_SHAPE;
+        p->ppsm = (int)ppsm;
+        p->gridm = ppsm * K * p->ctiles;
+        if (p->gridm > 0x7fffffffLL) return CGBN_ERR_SHAPE;
     }
     if (p->grid > 0x7fffffffLL || (long long)p->rows * C > (1LL << 33)) return CGBN_ERR_SHAPE;
     int G = 1;
@@ -233,13 +245,18 @@ template <typename T, int OP> void launch_reduce_t(const Plan& p, const SweepArg
 
 template <typename T, int EL> void launch_map_t(const Plan& p, const SweepArgs& A, hipStream_t st)
 {
-    dim3 grid((unsigned)p.grid), block(kThreads);
+    dim3 block(kThreads);
     if (p.layout == CGBN_NCHW) {
+        dim3 grid((unsigned)p.grid);
         if (p.wave_mode) hipLaunchKernelGGL((nchw_map_wave<T, EL>), grid, block, 0, st, A);
         else hipLaunchKernelGGL((nchw_map_block<T, EL>), grid, block, 0, st, A);
     } else {
-        if (p.vec == 1) hipLaunchKernelGGL((nhwc_map<T, 1, EL>), grid, block, 0, st, A);
-        else hipLaunchKernelGGL((nhwc_map<T, Elem<T>::VEC, EL>), grid, block, 0, st, A);
+        dim3 grid((unsigned)p.gridm);
+        SweepArgs B = A;              // the elementwise sweeps cut the pixel runs their own way
+        B.PL = p.PLm;
+        B.pps = p.ppsm;
+        if (p.vec == 1) hipLaunchKernelGGL((nhwc_map<T, 1, EL>), grid, block, 0, st, B);
+        else hipLaunchKernelGGL((nhwc_map<T, Elem<T>::VEC, EL>), grid, block, 0, st, B);
     }
 }
 
@@ -636,6 +653,7 @@ static long long* tuning_slot(const char* key)
     if (!std::strcmp(key, "chunk_bytes")) return &g_tune.chunk_bytes;
     if (!std::strcmp(key, "wave_plane_bytes")) return &g_tune.wave_plane_bytes;
     if (!std::strcmp(key, "piece_bytes")) return &g_tune.piece_bytes;
+    if (!std::strcmp(key, "map_piece_bytes")) return &g_tune.map_piece_bytes;
     if (!std::strcmp(key, "reverse")) return &g_tune.reverse;
     if (!std::strcmp(key, "nt_store")) return &g_tune.nt_store;
     if (!std::strcmp(key, "fused")) return &g_tune.fused;

@@ -466,16 +466,17 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
         const long long C = A.C;
         const int rpp = A.rpp;
         int i = r;
-        for (; i + 3 * rpp < npix; i += 4 * rpp) {
-            float xv[4][V], dv[4][V];
+        constexpr int UNR = OP == OP_BWD ? 4 : 8;        // loads in flight per lane and tensor
+        for (; i + (UNR - 1) * rpp < npix; i += UNR * rpp) {
+            float xv[UNR][V], dv[UNR][V];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) Access<T, V>::load(px + (long long)(i + u * rpp) * C, xv[u]);
+            for (int u = 0; u < UNR; ++u) Access<T, V>::load(px + (long long)(i + u * rpp) * C, xv[u]);
             if (OP == OP_BWD) {
 #pragma unroll
-                for (int u = 0; u < 4; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, dv[u]);
+                for (int u = 0; u < UNR; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, dv[u]);
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < UNR; ++u)
 #pragma unroll
                 for (int e = 0; e < V; ++e)
                     accumulate<OP>(kc[e], xv[u][e], OP == OP_BWD ? dv[u][e] : 0.f, a0[e], a1[e]);
@@ -601,16 +602,28 @@ __device__ __forceinline__ double shard_then_total(const float* pr, double* sh, 
 {
     const int G = A.G;
     const int gl = lane & (G - 1), gi = lane / G, spp = kWave / G;
+    constexpr int B = 8;                 // passes whose first loads are issued together
     double tot = 0.0;
-    for (int k0 = 0; k0 < A.K; k0 += spp) {
-        int k = k0 + gi;
-        double acc = 0.0;
-        if (k < A.K)
-            for (int r = gl; r < A.rps; r += G) acc += (double)pr[(size_t)k * A.rps + r];
-        for (int off = G >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
-        if (k < A.K) {
-            if (sh && gl == 0) sh[(size_t)k * A.C + c] = acc + shard_offset;
-            tot += acc;
+    for (int k0 = 0; k0 < A.K; k0 += B * spp) {
+        double acc[B];
+        // the first row of every pass: independent loads, one memory round trip for all B passes
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            int k = k0 + u * spp + gi;
+            bool have = k < A.K && gl < A.rps;
+            float v = pr[have ? (size_t)k * A.rps + gl : 0];
+            acc[u] = have ? (double)v : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < B; ++u) {
+            int k = k0 + u * spp + gi;
+            if (k < A.K)
+                for (int r = gl + G; r < A.rps; r += G) acc[u] += (double)pr[(size_t)k * A.rps + r];
+            for (int off = G >> 1; off >= 1; off >>= 1) acc[u] += __shfl_xor(acc[u], off);
+            if (k < A.K) {
+                if (sh && gl == 0) sh[(size_t)k * A.C + c] = acc[u] + shard_offset;
+                tot += acc[u];
+            }
         }
     }
     for (int off = kWave >> 1; off >= G; off >>= 1) tot += __shfl_xor(tot, off);

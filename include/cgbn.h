@@ -96,8 +96,10 @@ cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, cons
                           cgbn_dtype dtype, const float* mean_lo,
                           void* workspace, size_t workspace_bytes, void* stream);
 
-/* ---- The same path one step at a time (cgbn_forward and cgbn_backward run
- * exactly these kernels back to back).  Meant for tests and measurement. ---- */
+/* ---- The same path one step at a time, one sweep over the tensor per call.
+ * cgbn_forward and cgbn_backward run these kernels back to back where a shape
+ * does not qualify for their single-launch kernels (and always when the
+ * "fused" knob is 0).  Meant for tests and measurement. ---- */
 
 /* Algorithm 1 steps 1-3: s[k*C + c] = sum over shard k of x. */
 cgbn_status cgbn_shard_sum(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,

@@ -1,10 +1,10 @@
 // Register-resident CGBN for NCHW tensors: each activation value is read from
-// HBM once per direction and kept in VGPRs while the cross-shard reductions
-// complete.
+// HBM once per direction and kept on chip (VGPRs, plus some LDS for large
+// planes) while the cross-shard reductions complete.
 //
 // The multi-sweep kernels read x three times in the forward (sum, squared
 // deviations, normalise) and dy, x twice in the backward.  Here a workgroup
-// takes a *unit* -- up to 128 KiB of one channel -- into registers, writes its
+// takes a *unit* -- up to 152 KiB of one channel -- into registers, writes its
 // partial sums to the channel's rows, waits until every unit of the channel has
 // done so, reduces the rows itself (shard by shard, then across shards, in double
 // precision, the same arithmetic as combine_rows and the same in every
@@ -22,12 +22,15 @@
 // agent-scope loads, again if a sentinel is still there.  No fences, no store
 // acknowledgements on the path.
 //
-// Units.  Large planes are cut into tiles of up to 128 KiB (64 KiB per tensor in
-// the backward); a unit is one tile and leaves one row.  Small planes (one fits
-// a wavefront's share of the registers) are taken whole, one plane per
-// wavefront at a time, several planes of consecutive images per wavefront; a
-// unit is 4*P planes of one channel and leaves one row per plane.  Rows are
-// ordered by image, hence shard by shard.
+// Units.  Large planes are cut into equal tiles of up to 152 KiB (76 KiB per
+// tensor in the backward): 128 KiB in registers, and with 16-byte loads a
+// further 24 KiB in LDS, filled by global-to-LDS loads.  A unit is one tile and
+// leaves one row.  Small planes (one fits a wavefront's share of the registers)
+// are taken whole, one plane per wavefront at a time, P planes of consecutive
+// images per wavefront, each in LPPC register slots (a template parameter, the
+// smallest instantiated count that holds the plane); a unit is up to 4*P planes
+// of one channel and leaves one row per plane.  Rows are ordered by image, hence
+// shard by shard.
 //
 // Scheduling.  The grid is persistent and no larger than what is resident at
 // once; workgroup b takes units b, b + G, b + 2G, ... in channel-major order.

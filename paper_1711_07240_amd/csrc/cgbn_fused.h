@@ -76,7 +76,7 @@ struct FusedArgs {
     float* part1;
     double* sh0;          // [K][C]
     double* sh1;
-    unsigned* sync;       // [1] error word, [kSyncHeader ..) unit counters cnt1[C], cnt2[C], flags flag1[C], flag2[C]
+    unsigned* sync;       // [1] error word, [kSyncHeader ..) per-channel (or per-group) unit counters and flags
     unsigned long long* trace;   // only used in builds with CGBN_TRACE
     long long total_units;
     double M, inv_M_f64, eps, shard_count;
@@ -89,6 +89,13 @@ struct FusedArgs {
     int nt;
     unsigned spin_limit;
     unsigned plane_stride; // small planes: bytes between the same channel's planes of consecutive images
+    // channels-last kernels (cgbn_fused_nhwc.h)
+    float* stat0;         // [C] statistics handed from the reducing workgroups to the others
+    float* stat1;
+    float* stat2;
+    long long spix;       // pixels per shard
+    int groups, ups, PU;  // channel groups, units per shard, pixels per unit
+    unsigned row_bytes;   // bytes of one pixel (all channels)
 };
 
 constexpr unsigned kRowSentinel = 0xffffffffu;
@@ -218,15 +225,14 @@ __device__ __forceinline__ void count_in(unsigned* cnt, unsigned* flag, int U)
 // arrays of channel c into LDS, again until no sentinel is left (a row store may
 // still be in flight when the flag is seen).
 // Bounded: false if `spin_limit` polls were not enough.
-// `first` selects the arrays: rows of part0 (and part1 if Q == 2) for first == 0,
-// rows of part1 for first == 1.
+// Row r of the first array is rows0[r * stride] (rows1 likewise, used if Q == 2).
 template <int Q>
-__device__ __forceinline__ bool gather_rows(const FusedArgs& A, int c, const unsigned* flag, ReduceLds& L,
-                                            int first = 0)
+__device__ __forceinline__ bool gather_rows(const FusedArgs& A, const float* rows0, const float* rows1, int stride,
+                                            const unsigned* flag, ReduceLds& L)
 {
     const int t = threadIdx.x;
-    const unsigned* p0 = reinterpret_cast<const unsigned*>((first ? A.part1 : A.part0) + (size_t)c * A.rows);
-    const unsigned* p1 = reinterpret_cast<const unsigned*>(A.part1 + (size_t)c * A.rows);
+    const unsigned* p0 = reinterpret_cast<const unsigned*>(rows0);
+    const unsigned* p1 = reinterpret_cast<const unsigned*>(rows1);
     unsigned polls = 0;
     if (t == 0) {
         while (ld_agent(flag) == 0u && polls < A.spin_limit) {
@@ -239,11 +245,11 @@ __device__ __forceinline__ bool gather_rows(const FusedArgs& A, int c, const uns
         if (t == 0) L.missing = 0;
         __syncthreads();              // lane 0 has seen the count; LDS rows are free to overwrite
         for (int r = t; r < A.rows; r += kThreads) {
-            unsigned b0 = ld_agent(p0 + r);
+            unsigned b0 = ld_agent(p0 + (size_t)r * stride);
             missing |= b0 == kRowSentinel;
             L.rows[0][r] = __uint_as_float(b0);
             if (Q == 2) {
-                unsigned b1 = ld_agent(p1 + r);
+                unsigned b1 = ld_agent(p1 + (size_t)r * stride);
                 missing |= b1 == kRowSentinel;
                 L.rows[1][r] = __uint_as_float(b1);
             }
@@ -476,7 +482,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
         // prove to run stops it from hoisting that block's index arithmetic out of the
         // unit loop, which would push the register-resident unit into scratch memory.
         if (A.rows > 0) {
-            ok1 = gather_rows<1>(A, c, A.sync + kSyncHeader + 2 * A.C + c, lds);
+            ok1 = gather_rows<1>(A, A.part0 + (size_t)c * A.rows, nullptr, 1, A.sync + kSyncHeader + 2 * A.C + c, lds);
             CGBN_STAMP(2);
             reduce_rows<1, ST_MEAN>(A, c, lds, (double)pivot, g.u == 0);
         }
@@ -536,7 +542,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
         // ---- steps 9-10: reduce to the variance and 1/sqrt(var + eps)
         bool ok2 = false;
         if (A.rows > 0) {
-            ok2 = gather_rows<1>(A, c, A.sync + kSyncHeader + 3 * A.C + c, lds, 1);
+            ok2 = gather_rows<1>(A, A.part1 + (size_t)c * A.rows, nullptr, 1, A.sync + kSyncHeader + 3 * A.C + c, lds);
             CGBN_STAMP(5);
             reduce_rows<1, ST_INVSTD>(A, c, lds, 0.0, g.u == 0, 1);
         }
@@ -680,7 +686,8 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
         CGBN_STAMP(1);
         bool ok1 = false;
         if (A.rows > 0) {
-            ok1 = gather_rows<2>(A, c, A.sync + kSyncHeader + 2 * A.C + c, lds);
+            ok1 = gather_rows<2>(A, A.part0 + (size_t)c * A.rows, A.part1 + (size_t)c * A.rows, 1,
+                                  A.sync + kSyncHeader + 2 * A.C + c, lds);
             CGBN_STAMP(2);
             reduce_rows<2, ST_SUMS>(A, c, lds, 0.0, g.u == 0);
         }

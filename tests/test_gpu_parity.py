@@ -18,10 +18,12 @@ pytestmark = pytest.mark.gpu
 def path(request):
     """Every test runs twice: with the register-resident single-launch kernels
     (where the shape allows them) and with the multi-sweep kernels only."""
-    old = L.cgbn_get_tuning("fused")
+    old = L.cgbn_get_tuning("fused"), L.cgbn_get_tuning("fused_nhwc")
     L.cgbn_set_tuning("fused", request.param)
+    L.cgbn_set_tuning("fused_nhwc", 2)      # channels-last: wherever the shape allows, not only where it pays
     yield request.param
-    L.cgbn_set_tuning("fused", old)
+    L.cgbn_set_tuning("fused", old[0])
+    L.cgbn_set_tuning("fused_nhwc", old[1])
 
 
 def oracle_all(x, dy, gamma, beta, eps, layout, dtype):
@@ -78,6 +80,13 @@ SMALL = [
     ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane90000", dict(N=2, C=2, H=300, W=300, K=2, layout="NCHW", dtype="bf16")),
+    # channels-last shapes that qualify for the single-launch kernels (128-byte channel groups)
+    ("nhwc-f32-c64", dict(N=4, C=64, H=19, W=23, K=2, layout="NHWC", dtype="f32")),
+    ("nhwc-f32-c32-two-units-per-shard", dict(N=3, C=32, H=37, W=41, K=3, layout="NHWC", dtype="f32")),
+    ("nhwc-f32-c96-few-units", dict(N=2, C=96, H=3, W=5, K=2, layout="NHWC", dtype="f32")),
+    ("nhwc-f32-c256-long-shard", dict(N=2, C=256, H=60, W=70, K=1, layout="NHWC", dtype="f32")),
+    ("nhwc-bf16-c128", dict(N=4, C=128, H=33, W=35, K=2, layout="NHWC", dtype="bf16")),
+    ("nhwc-bf16-c64-long-shard", dict(N=2, C=64, H=50, W=41, K=2, layout="NHWC", dtype="bf16")),
     # degenerate shapes
     ("one-image-per-shard", dict(N=6, C=4, H=8, W=8, K=6, layout="NCHW", dtype="f32")),
     ("single-image", dict(N=1, C=3, H=20, W=20, K=1, layout="NCHW", dtype="f32")),
@@ -134,7 +143,7 @@ def test_hand_examples_on_gpu():
 def test_step_entry_points_match_algorithm_1(layout, dtype):
     """Each step of Algorithm 1 on its own: the device sums s, v (and a, b of the
     backward) against the oracle's shard-by-shard walk."""
-    wl = BASE.scaled(N=8, C=24, H=30, W=33, K=4, layout=layout, dtype=dtype)
+    wl = BASE.scaled(N=8, C=64, H=30, W=33, K=4, layout=layout, dtype=dtype)
     d = synth.make_inputs(wl)
     N, C, H, W, K = wl.N, wl.C, wl.H, wl.W, wl.K
     x64, dy64 = widen(d["x"], dtype), widen(d["dy"], dtype)
@@ -194,9 +203,9 @@ def test_shard_count_changes_only_rounding_and_runs_are_reproducible():
         assert np.allclose(r["y"], outs[0]["y"], atol=2e-6)
 
 
-@pytest.mark.parametrize("layout,dtype", [("NCHW", "f32"), ("NHWC", "bf16")])
+@pytest.mark.parametrize("layout,dtype", [("NCHW", "f32"), ("NHWC", "bf16"), ("NHWC", "f32")])
 def test_in_place(layout, dtype):
-    wl = BASE.scaled(N=4, C=16, H=23, W=37, K=2, layout=layout, dtype=dtype)
+    wl = BASE.scaled(N=4, C=64, H=23, W=37, K=2, layout=layout, dtype=dtype)
     d = synth.make_inputs(wl)
     p = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, layout, dtype, wl.K)
     p.forward(); p.backward()

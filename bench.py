@@ -138,13 +138,33 @@ def measure_workload(layer, torch, steps, warmup):
         layer.step()
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
+    per_step = time_calls(torch, layer.step, 0, steps)
     fwd = statistics.median(time_calls(torch, layer.forward, 2, max(5, steps // 2)))
     bwd = statistics.median(time_calls(torch, layer.backward, 2, max(5, steps // 2)))
     return dict(
         workload=wl.name, ms_per_step=wall_ms, fwd_ms=fwd, bwd_ms=bwd,
+        step_ms_median=statistics.median(per_step), step_ms_min=min(per_step), step_ms_max=max(per_step),
+        single_launch=dict(forward=layer.cgbn.cgbn_get_tuning("last_forward_fused"),
+                           backward=layer.cgbn.cgbn_get_tuning("last_backward_fused")),
         effective_GBps=9 * Sb / wall_ms / 1e6, pct_of_peak=9 * Sb / wall_ms / 1e6 / PEAK_GBPS * 100,
         floor_GBps=5 * Sb / wall_ms / 1e6,
         fwd_effective_GBps=4 * Sb / fwd / 1e6, bwd_effective_GBps=5 * Sb / bwd / 1e6)
+
+
+def measure_rotating(layer, torch, cgbn, steps, sets=4):
+    """ms per step when consecutive steps work on different buffer sets, so that
+    nothing a step left in the memory-side cache serves the next one."""
+    wl = layer.wl
+    layers = [layer] + [Layer(wl, torch, cgbn, layer.x.clone(), layer.dy.clone(), layer.gamma, layer.beta)
+                        for _ in range(sets - 1)]
+    for l in layers:
+        l.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(steps):
+        layers[i % sets].step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
 
 
 def cpu_baseline(wl, synth, budget_s=12.0):
@@ -264,6 +284,10 @@ def main():
         log(f"[bench] secondary workload {name}")
         l2 = Layer(w2, torch, cgbn, *device_inputs_fast(w2, torch, synth, dev))
         others.append(measure_workload(l2, torch, max(5, args.steps // 5), max(2, args.warmup // 2)))
+        if 4 * w2.S * w2.elem_bytes <= (2 << 30):
+            # tensors near the size of the memory-side cache (256 MB): the figure above re-uses one
+            # buffer set ("warm"), this one rotates over four ("cold")
+            others[-1]["ms_per_step_rotating_4_buffer_sets"] = measure_rotating(l2, torch, cgbn, max(8, args.steps // 5))
         del l2
         torch.cuda.empty_cache()
 
@@ -282,11 +306,14 @@ def main():
                    "step": "cgbn_forward + cgbn_backward", "algorithmic_bytes": 9 * Sb,
                    "tuning": {k: cgbn.cgbn_get_tuning(k) for k in
                               ("chunk_bytes", "wave_plane_bytes", "piece_bytes", "map_piece_bytes", "reverse", "nt_store", "fused",
-                               "last_forward_fused", "last_backward_fused")}},
+                               "fused_nhwc")},
+                   "single_launch": head["single_launch"]},
         "pct_of_peak": head["pct_of_peak"], "fwd_ms": head["fwd_ms"], "bwd_ms": head["bwd_ms"],
         "floor_GBps": head["floor_GBps"],
+        "step_ms": {"median": head["step_ms_median"], "min": head["step_ms_min"], "max": head["step_ms_max"]},
         "sweeps": sweeps, "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,
-        "device": torch.cuda.get_device_name(0),
+        "device": torch.cuda.get_device_name(0), "hip": torch.version.hip,
+        "compute_units": torch.cuda.get_device_properties(0).multi_processor_count,
     }
     print(json.dumps(out), flush=True)
 

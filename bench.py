@@ -268,6 +268,16 @@ def main():
                         frac=sweeps[dom]["GBps"] / PEAK_GBPS, traffic=load_traffic(f"{wl.name}.{dom}"),
                         avg_ms=sweeps[dom]["ms"], algorithmic_bytes=3 * Sb)
 
+    # fixed-statistics mode on the same tensors: one sweep each way, 2*S*b bytes per launch
+    fv = layer.invstd.double().pow(-2).float()                      # variances of the right size for this data
+    frozen = {}
+    for name, fn in (("frozen_forward", lambda: cgbn.cgbn_frozen_forward(
+                          layer.x, *layer.shape, wl.layout, wl.dtype, layer.mean, fv, layer.gamma, layer.beta, wl.eps, layer.y)),
+                     ("frozen_backward", lambda: cgbn.cgbn_frozen_backward(
+                          layer.dy, *layer.shape, wl.layout, wl.dtype, fv, layer.gamma, wl.eps, layer.dx))):
+        ms = statistics.mean(time_calls(torch, fn, 3, max(10, args.steps // 2)))
+        frozen[name] = dict(ms=ms, GBps=2 * Sb / ms / 1e6, frac_of_peak=2 * Sb / ms / 1e6 / PEAK_GBPS)
+
     if args.calibrate:
         nb = 1 << 30
         a, b = torch.empty(nb, dtype=torch.uint8, device=dev), torch.empty(nb, dtype=torch.uint8, device=dev)
@@ -311,7 +321,7 @@ def main():
         "pct_of_peak": head["pct_of_peak"], "fwd_ms": head["fwd_ms"], "bwd_ms": head["bwd_ms"],
         "floor_GBps": head["floor_GBps"],
         "step_ms": {"median": head["step_ms_median"], "min": head["step_ms_min"], "max": head["step_ms_max"]},
-        "sweeps": sweeps, "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,
+        "sweeps": sweeps, "fixed_statistics_mode": frozen, "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,
         "device": torch.cuda.get_device_name(0), "hip": torch.version.hip,
         "compute_units": torch.cuda.get_device_properties(0).multi_processor_count,
     }

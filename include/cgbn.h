@@ -58,7 +58,8 @@ typedef enum cgbn_status {
     CGBN_ERR_WORKSPACE = 6,  /* workspace NULL, misaligned (256 B) or too small */
     CGBN_ERR_ALIGN = 7,      /* an activation tensor is not 16-byte aligned */
     CGBN_ERR_HIP = 8,        /* the HIP runtime refused a launch */
-    CGBN_ERR_TUNING = 9      /* unknown tuning key or value out of range */
+    CGBN_ERR_TUNING = 9,     /* unknown tuning key or value out of range */
+    CGBN_ERR_MOMENTUM = 10   /* momentum outside [0, 1] */
 } cgbn_status;
 
 typedef enum cgbn_layout { CGBN_NCHW = 0, CGBN_NHWC = 1 } cgbn_layout;
@@ -142,6 +143,36 @@ cgbn_status cgbn_backward_dx(const void* dy, const void* x, int N, int C, int H,
                              const float* mean, const float* mean_lo, const float* invstd,
                              const float* gamma, const float* dgamma, const float* dbeta,
                              void* dx, void* stream);
+
+/* ---- Fixed-statistics ("frozen") mode: the layer the paper's baseline detectors use
+ * (section 3.1; opening of section 3.3; Table 3, row "16-base", BN size 0), where the
+ * statistics are constants computed beforehand.  One elementwise sweep each; no
+ * workspace.  The paper does not say how the constants come about; the update below is
+ * the exponential moving average of the batch-normalization work section 3.3 builds on,
+ * with `momentum` and `unbiased` left to the caller. ---- */
+
+/* y = gamma*(x - fixed_mean)/sqrt(fixed_var + eps) + beta: the formula of Algorithm 1's last
+ * step with constants for the statistics.  fixed_mean[C], fixed_var[C] (variances, not
+ * their inverse roots), gamma[C], beta[C].  y may be exactly x. */
+cgbn_status cgbn_frozen_forward(const void* x, int N, int C, int H, int W, cgbn_layout layout,
+                                cgbn_dtype dtype, const float* fixed_mean, const float* fixed_var,
+                                const float* gamma, const float* beta, float eps,
+                                void* y, void* stream);
+
+/* Its backward.  Statistics and affine parameters are constants of the layer, so
+ * dx = dy*gamma/sqrt(fixed_var + eps) and there is no dgamma/dbeta.  dx may be exactly dy. */
+cgbn_status cgbn_frozen_backward(const void* dy, int N, int C, int H, int W, cgbn_layout layout,
+                                 cgbn_dtype dtype, const float* fixed_var, const float* gamma,
+                                 float eps, void* dx, void* stream);
+
+/* After a cgbn_forward with the same eps over M = N*H*W values per channel:
+ *   running_mean <- (1-momentum)*running_mean + momentum*(mean + mean_lo)
+ *   running_var  <- (1-momentum)*running_var  + momentum*var*(unbiased ? M/(M-1) : 1)
+ * in place, with var = 1/invstd^2 - eps (accurate to about 2e-7*(var + eps)).  mean_lo may
+ * be NULL.  0 <= momentum <= 1, else CGBN_ERR_MOMENTUM; unbiased needs M >= 2. */
+cgbn_status cgbn_update_running_stats(const float* mean, const float* mean_lo, const float* invstd,
+                                      float eps, long long M, int C, float momentum, int unbiased,
+                                      float* running_mean, float* running_var, void* stream);
 
 /* ---- housekeeping ---- */
 

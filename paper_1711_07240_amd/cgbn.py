@@ -45,6 +45,9 @@ SIGNATURES = {
                                  + [_c_p] * 5 + [_c_p, _c_sz, _c_p]),
     "cgbn_backward_reduce": (_c_int, [_c_p, _c_p, _c_int, _c_int, _c_p, _c_p, _c_p]),
     "cgbn_backward_dx": (_c_int, [_c_p, _c_p] + [_c_int] * 4 + [_c_int, _c_int] + [_c_p] * 8),
+    "cgbn_frozen_forward": (_c_int, [_c_p] + [_c_int] * 4 + [_c_int, _c_int] + [_c_p] * 4 + [_c_f, _c_p, _c_p]),
+    "cgbn_frozen_backward": (_c_int, [_c_p] + [_c_int] * 4 + [_c_int, _c_int] + [_c_p] * 2 + [_c_f, _c_p, _c_p]),
+    "cgbn_update_running_stats": (_c_int, [_c_p, _c_p, _c_p, _c_f, _c_ll, _c_int, _c_f, _c_int, _c_p, _c_p, _c_p]),
     "cgbn_calibration_copy": (_c_int, [_c_p, _c_p, _c_sz, _c_p]),
     "cgbn_status_string": (ctypes.c_char_p, [_c_int]),
     "cgbn_set_tuning": (_c_int, [ctypes.c_char_p, _c_ll]),
@@ -190,6 +193,25 @@ def cgbn_backward_dx(dy, x, N, C, H, W, layout, dtype, mean, mean_lo, invstd, ga
                                   _enum(DTYPES, dtype), _ptr(mean), _ptr(mean_lo), _ptr(invstd),
                                   _ptr(gamma), _ptr(dgamma), _ptr(dbeta), _ptr(dx), _stream(stream)),
            "cgbn_backward_dx")
+
+
+def cgbn_frozen_forward(x, N, C, H, W, layout, dtype, fixed_mean, fixed_var, gamma, beta, eps, y, stream=None) -> None:
+    _check(lib().cgbn_frozen_forward(_ptr(x), N, C, H, W, _enum(LAYOUTS, layout), _enum(DTYPES, dtype),
+                                     _ptr(fixed_mean), _ptr(fixed_var), _ptr(gamma), _ptr(beta), float(eps),
+                                     _ptr(y), _stream(stream)), "cgbn_frozen_forward")
+
+
+def cgbn_frozen_backward(dy, N, C, H, W, layout, dtype, fixed_var, gamma, eps, dx, stream=None) -> None:
+    _check(lib().cgbn_frozen_backward(_ptr(dy), N, C, H, W, _enum(LAYOUTS, layout), _enum(DTYPES, dtype),
+                                      _ptr(fixed_var), _ptr(gamma), float(eps), _ptr(dx), _stream(stream)),
+           "cgbn_frozen_backward")
+
+
+def cgbn_update_running_stats(mean, mean_lo, invstd, eps, M, C, momentum, unbiased, running_mean, running_var,
+                              stream=None) -> None:
+    _check(lib().cgbn_update_running_stats(_ptr(mean), _ptr(mean_lo), _ptr(invstd), float(eps), int(M), int(C),
+                                           float(momentum), int(bool(unbiased)), _ptr(running_mean),
+                                           _ptr(running_var), _stream(stream)), "cgbn_update_running_stats")
 
 
 def cgbn_calibration_copy(src, dst, nbytes, stream=None) -> None:

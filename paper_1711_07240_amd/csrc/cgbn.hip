@@ -305,8 +305,12 @@ cgbn_status launch_reduce(int op, const Plan& p, const SweepArgs& A, hipStream_t
 cgbn_status launch_map(int el, const Plan& p, const SweepArgs& A, hipStream_t st)
 {
     const bool f32 = p.dtype == CGBN_F32;
-    if (el == EL_NORM) f32 ? launch_map_t<float, EL_NORM>(p, A, st) : launch_map_t<bf16_t, EL_NORM>(p, A, st);
-    else               f32 ? launch_map_t<float, EL_DX>(p, A, st)   : launch_map_t<bf16_t, EL_DX>(p, A, st);
+    switch (el) {
+    case EL_NORM:   f32 ? launch_map_t<float, EL_NORM>(p, A, st)   : launch_map_t<bf16_t, EL_NORM>(p, A, st); break;
+    case EL_DX:     f32 ? launch_map_t<float, EL_DX>(p, A, st)     : launch_map_t<bf16_t, EL_DX>(p, A, st); break;
+    case EL_FROZEN: f32 ? launch_map_t<float, EL_FROZEN>(p, A, st) : launch_map_t<bf16_t, EL_FROZEN>(p, A, st); break;
+    default:        f32 ? launch_map_t<float, EL_SCALE>(p, A, st)  : launch_map_t<bf16_t, EL_SCALE>(p, A, st); break;
+    }
     return launched();
 }
 
@@ -591,6 +595,48 @@ cgbn_status cgbn_backward_dx(const void* dy, const void* x, int N, int C, int H,
     return launch_map(EL_DX, p, A, static_cast<hipStream_t>(stream));
 }
 
+cgbn_status cgbn_frozen_forward(const void* x, int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype,
+                                const float* fixed_mean, const float* fixed_var,
+                                const float* gamma, const float* beta, float eps, void* y, void* stream)
+{
+    if (!x || !fixed_mean || !fixed_var || !gamma || !beta || !y) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, 1, &p));
+    if (!eps_ok(eps)) return CGBN_ERR_EPS;
+    if (!aligned16(x) || !aligned16(y)) return CGBN_ERR_ALIGN;
+    SweepArgs A = sweep_args(p);
+    A.x = x; A.out = y; A.mean = fixed_mean; A.invstd = fixed_var; A.gamma = gamma; A.beta = beta; A.eps = eps;
+    return launch_map(EL_FROZEN, p, A, static_cast<hipStream_t>(stream));
+}
+
+cgbn_status cgbn_frozen_backward(const void* dy, int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype,
+                                 const float* fixed_var, const float* gamma, float eps, void* dx, void* stream)
+{
+    if (!dy || !fixed_var || !gamma || !dx) return CGBN_ERR_NULL;
+    Plan p;
+    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, 1, &p));
+    if (!eps_ok(eps)) return CGBN_ERR_EPS;
+    if (!aligned16(dy) || !aligned16(dx)) return CGBN_ERR_ALIGN;
+    SweepArgs A = sweep_args(p);
+    A.x = dy; A.out = dx; A.invstd = fixed_var; A.gamma = gamma; A.eps = eps;
+    return launch_map(EL_SCALE, p, A, static_cast<hipStream_t>(stream));
+}
+
+cgbn_status cgbn_update_running_stats(const float* mean, const float* mean_lo, const float* invstd, float eps,
+                                      long long M, int C, float momentum, int unbiased,
+                                      float* running_mean, float* running_var, void* stream)
+{
+    if (!mean || !invstd || !running_mean || !running_var) return CGBN_ERR_NULL;
+    if (C < 1 || M < 1 || (unbiased && M < 2)) return CGBN_ERR_SHAPE;
+    if (!eps_ok(eps)) return CGBN_ERR_EPS;
+    if (!(momentum >= 0.f && momentum <= 1.f)) return CGBN_ERR_MOMENTUM;
+    const double unbias = unbiased ? (double)M / (double)(M - 1) : 1.0;
+    dim3 grid((unsigned)((C + kThreads - 1) / kThreads)), block(kThreads);
+    hipLaunchKernelGGL(running_update, grid, block, 0, static_cast<hipStream_t>(stream),
+                       mean, mean_lo, invstd, (double)eps, unbias, (double)momentum, running_mean, running_var, C);
+    return launched();
+}
+
 cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
                          const float* gamma, const float* beta, float eps,
                          void* y, float* mean, float* invstd,
@@ -692,6 +738,7 @@ const char* cgbn_status_string(cgbn_status status)
     case CGBN_ERR_ALIGN: return "activation tensors must be 16-byte aligned";
     case CGBN_ERR_HIP: return "the HIP runtime refused a launch";
     case CGBN_ERR_TUNING: return "unknown tuning key or value out of range";
+    case CGBN_ERR_MOMENTUM: return "momentum outside [0, 1]";
     }
     return "unknown status";
 }

@@ -8,6 +8,8 @@
 //   reduce  OP_BWD    sum dy, sum dy*xhat         backward device sums
 //   map     EL_NORM   y  = gamma*(x-mean)*invstd + beta            step 11
 //   map     EL_DX     dx = gamma*invstd*(dy - dbeta/M - xhat*dgamma/M)
+//   map     EL_FROZEN y  = gamma*(x-m)/sqrt(s2+eps) + beta   fixed statistics m, s2 (sections 3.1, 3.3)
+//   map     EL_SCALE  dx = dy*gamma/sqrt(s2+eps)             backward of the fixed-statistics layer
 // A reduce sweep leaves one float per (channel, row) in `part`, where the rows
 // of a channel are ordered shard by shard; combine_rows then adds the rows of a
 // shard (the device sum of Algorithm 1) and the shards (its reduce step) in
@@ -23,7 +25,7 @@ constexpr int kThreads = 256;   // 4 wavefronts per workgroup
 constexpr int kWave = 64;
 
 enum { OP_SUM = 0, OP_SQDEV = 1, OP_BWD = 2 };
-enum { EL_NORM = 0, EL_DX = 1 };
+enum { EL_NORM = 0, EL_DX = 1, EL_FROZEN = 2, EL_SCALE = 3 };
 enum { CM_MEAN = 0, CM_INVSTD = 1, CM_BWD = 2, CM_SHARDS1 = 3, CM_SHARDS2 = 4 };
 
 struct bf16_t { uint16_t bits; };
@@ -53,6 +55,7 @@ struct SweepArgs {
     long long spix;           // pixels per shard
     long long pivot_stride;   // elements between the first values of consecutive channels
     float inv_M;
+    float eps;                // fixed-statistics maps: `invstd` then points at variances
     int reverse;              // walk the grid backwards
     int nt;                   // non-temporal stores
 };
@@ -208,6 +211,17 @@ template <typename T, int OP> __device__ __forceinline__ ChanConst reduce_consts
 template <int EL> __device__ __forceinline__ ChanConst map_consts(const SweepArgs& A, int c)
 {
     ChanConst k;
+    if (EL == EL_FROZEN || EL == EL_SCALE) {
+        // fixed statistics: `invstd` points at the variances; the root and the division are
+        // correctly rounded float operations, once per thread and channel
+        k.istd = 1.0f / sqrtf(A.invstd[c] + A.eps);
+        k.g = A.gamma[c] * k.istd;
+        k.mu = EL == EL_FROZEN ? A.mean[c] : 0.f;
+        k.b = EL == EL_FROZEN ? A.beta[c] : 0.f;
+        k.mulo = 0.f;
+        k.c2 = 0.f;
+        return k;
+    }
     k.mu = A.mean[c];
     k.mulo = A.mean_lo ? A.mean_lo[c] : 0.f;
     k.istd = A.invstd[c];
@@ -238,6 +252,8 @@ template <int OP> __device__ __forceinline__ void accumulate(const ChanConst& k,
 
 template <int EL> __device__ __forceinline__ float map_value(const ChanConst& k, float xv, float dyv)
 {
+    if (EL == EL_SCALE) return xv * k.g;
+    if (EL == EL_FROZEN) return (xv - k.mu) * k.g + k.b;
     float d = (xv - k.mu) - k.mulo;
     if (EL == EL_NORM) return d * k.g + k.b;
     return k.g * ((dyv - k.b) - (d * k.istd) * k.c2);
@@ -685,6 +701,23 @@ __global__ __launch_bounds__(kThreads) void combine_shards(const double* s0, con
 
 // Plain copy of `nvec` 16-byte vectors, 8 per thread: reads and writes a known
 // number of bytes, for calibrating hardware traffic counters.
+// Exponential moving average of the pooled statistics (one thread per channel, float64).
+// The biased batch variance is recovered from invstd: var = 1/invstd^2 - eps.
+__global__ __launch_bounds__(kThreads) void running_update(const float* mean, const float* mean_lo, const float* invstd,
+                                                           double eps, double unbias, double momentum,
+                                                           float* running_mean, float* running_var, int C)
+{
+    int c = blockIdx.x * kThreads + threadIdx.x;
+    if (c >= C) return;
+    double mu = (double)mean[c] + (mean_lo ? (double)mean_lo[c] : 0.0);
+    double is = (double)invstd[c];
+    double var = 1.0 / (is * is) - eps;
+    if (var < 0.0) var = 0.0;                       // rounding of invstd when var << eps; NaN stays NaN
+    double keep = 1.0 - momentum;
+    running_mean[c] = (float)(keep * (double)running_mean[c] + momentum * mu);
+    running_var[c] = (float)(keep * (double)running_var[c] + momentum * (var * unbias));
+}
+
 __global__ __launch_bounds__(kThreads) void calibration_copy(const u32x4* src, u32x4* dst, size_t nvec)
 {
     size_t i = (size_t)blockIdx.x * (kThreads * 8) + threadIdx.x;

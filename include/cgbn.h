@@ -97,6 +97,30 @@ cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, cons
                           cgbn_dtype dtype, const float* mean_lo,
                           void* workspace, size_t workspace_bytes, void* stream);
 
+/* ---- CGBN followed by a shortcut add and a ReLU, the two placements of a normalization
+ * layer in the detector's backbone (ResNet-50, section 4): y = max(0, z) inside a block,
+ * y = max(0, z + shortcut) at a block's end, z being Algorithm 1's output.  The paper does
+ * not discuss the activation; fusing it here saves the separate sweeps over y and dy. ---- */
+
+/* As cgbn_forward, then y = max(0, z + shortcut).  `shortcut` (same shape, layout and
+ * dtype as x) may be NULL: y = max(0, z).  The statistics are those of x alone.
+ * y may be exactly x or exactly shortcut. */
+cgbn_status cgbn_forward_relu(const void* x, const void* shortcut, int N, int C, int H, int W,
+                              cgbn_layout layout, int K, const float* gamma, const float* beta, float eps,
+                              void* y, float* mean, float* invstd, cgbn_dtype dtype, float* mean_lo,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Its backward.  `y` is the output cgbn_forward_relu stored: gradient passes where y > 0
+ * (dz = dy there, 0 elsewhere), then dbeta, dgamma, dx as in cgbn_backward with dz for dy.
+ * `dshortcut`, if not NULL, receives dz (the gradient of the shortcut).  dx may be exactly
+ * dy, or dshortcut may be exactly dy; dx and dshortcut must differ. */
+cgbn_status cgbn_backward_relu(const void* dy, const void* y, const void* x,
+                               const float* mean, const float* invstd, const float* gamma,
+                               void* dx, void* dshortcut, float* dgamma, float* dbeta,
+                               int N, int C, int H, int W, cgbn_layout layout, int K,
+                               cgbn_dtype dtype, const float* mean_lo,
+                               void* workspace, size_t workspace_bytes, void* stream);
+
 /* ---- The same path one step at a time, one sweep over the tensor per call.
  * cgbn_forward and cgbn_backward run these kernels back to back where a shape
  * does not qualify for their single-launch kernels (and always when the

@@ -34,6 +34,10 @@ SIGNATURES = {
                               _c_p, _c_p, _c_p, _c_int, _c_p, _c_p, _c_sz, _c_p]),
     "cgbn_backward": (_c_int, [_c_p] * 8 + [_c_int] * 4 + [_c_int, _c_int, _c_int, _c_p,
                                _c_p, _c_sz, _c_p]),
+    "cgbn_forward_relu": (_c_int, [_c_p, _c_p] + [_c_int] * 4 + [_c_int, _c_int, _c_p, _c_p, _c_f,
+                                   _c_p, _c_p, _c_p, _c_int, _c_p, _c_p, _c_sz, _c_p]),
+    "cgbn_backward_relu": (_c_int, [_c_p] * 10 + [_c_int] * 4 + [_c_int, _c_int, _c_int, _c_p,
+                                    _c_p, _c_sz, _c_p]),
     "cgbn_shard_sum": (_c_int, [_c_p] + [_c_int] * 4 + [_c_int, _c_int, _c_int, _c_p,
                                 _c_p, _c_sz, _c_p]),
     "cgbn_reduce_mean": (_c_int, [_c_p, _c_int, _c_int, _c_ll, _c_p, _c_p, _c_p]),
@@ -141,6 +145,23 @@ def cgbn_backward(dy, x, mean, invstd, gamma, dx, dgamma, dbeta, N, C, H, W, lay
                                _ptr(dgamma), _ptr(dbeta), N, C, H, W, _enum(LAYOUTS, layout), K,
                                _enum(DTYPES, dtype), _ptr(mean_lo), _ptr(workspace), wb,
                                _stream(stream)), "cgbn_backward")
+
+
+def cgbn_forward_relu(x, shortcut, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd,
+                      dtype="f32", mean_lo=None, workspace=None, workspace_bytes=None, stream=None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None and workspace is not None else (workspace_bytes or 0)
+    _check(lib().cgbn_forward_relu(_ptr(x), _ptr(shortcut), N, C, H, W, _enum(LAYOUTS, layout), K, _ptr(gamma),
+                                   _ptr(beta), float(eps), _ptr(y), _ptr(mean), _ptr(invstd), _enum(DTYPES, dtype),
+                                   _ptr(mean_lo), _ptr(workspace), wb, _stream(stream)), "cgbn_forward_relu")
+
+
+def cgbn_backward_relu(dy, y, x, mean, invstd, gamma, dx, dshortcut, dgamma, dbeta, N, C, H, W, layout, K,
+                       dtype="f32", mean_lo=None, workspace=None, workspace_bytes=None, stream=None) -> None:
+    wb = _nbytes(workspace) if workspace_bytes is None and workspace is not None else (workspace_bytes or 0)
+    _check(lib().cgbn_backward_relu(_ptr(dy), _ptr(y), _ptr(x), _ptr(mean), _ptr(invstd), _ptr(gamma), _ptr(dx),
+                                    _ptr(dshortcut), _ptr(dgamma), _ptr(dbeta), N, C, H, W,
+                                    _enum(LAYOUTS, layout), K, _enum(DTYPES, dtype), _ptr(mean_lo),
+                                    _ptr(workspace), wb, _stream(stream)), "cgbn_backward_relu")
 
 
 def cgbn_shard_sum(x, N, C, H, W, layout, K, dtype, s, workspace, workspace_bytes=None, stream=None) -> None:

@@ -297,7 +297,8 @@ cgbn_status launch_reduce(int op, const Plan& p, const SweepArgs& A, hipStream_t
     switch (op) {
     case OP_SUM:   f32 ? launch_reduce_t<float, OP_SUM>(p, A, st)   : launch_reduce_t<bf16_t, OP_SUM>(p, A, st); break;
     case OP_SQDEV: f32 ? launch_reduce_t<float, OP_SQDEV>(p, A, st) : launch_reduce_t<bf16_t, OP_SQDEV>(p, A, st); break;
-    default:       f32 ? launch_reduce_t<float, OP_BWD>(p, A, st)   : launch_reduce_t<bf16_t, OP_BWD>(p, A, st); break;
+    case OP_BWD:   f32 ? launch_reduce_t<float, OP_BWD>(p, A, st)   : launch_reduce_t<bf16_t, OP_BWD>(p, A, st); break;
+    default:       f32 ? launch_reduce_t<float, OP_BWD_RELU>(p, A, st) : launch_reduce_t<bf16_t, OP_BWD_RELU>(p, A, st); break;
     }
     return launched();
 }
@@ -309,6 +310,9 @@ cgbn_status launch_map(int el, const Plan& p, const SweepArgs& A, hipStream_t st
     case EL_NORM:   f32 ? launch_map_t<float, EL_NORM>(p, A, st)   : launch_map_t<bf16_t, EL_NORM>(p, A, st); break;
     case EL_DX:     f32 ? launch_map_t<float, EL_DX>(p, A, st)     : launch_map_t<bf16_t, EL_DX>(p, A, st); break;
     case EL_FROZEN: f32 ? launch_map_t<float, EL_FROZEN>(p, A, st) : launch_map_t<bf16_t, EL_FROZEN>(p, A, st); break;
+    case EL_NORM_RELU: f32 ? launch_map_t<float, EL_NORM_RELU>(p, A, st) : launch_map_t<bf16_t, EL_NORM_RELU>(p, A, st); break;
+    case EL_NORM_ADD_RELU: f32 ? launch_map_t<float, EL_NORM_ADD_RELU>(p, A, st) : launch_map_t<bf16_t, EL_NORM_ADD_RELU>(p, A, st); break;
+    case EL_DX_RELU: f32 ? launch_map_t<float, EL_DX_RELU>(p, A, st) : launch_map_t<bf16_t, EL_DX_RELU>(p, A, st); break;
     default:        f32 ? launch_map_t<float, EL_SCALE>(p, A, st)  : launch_map_t<bf16_t, EL_SCALE>(p, A, st); break;
     }
     return launched();
@@ -637,17 +641,21 @@ cgbn_status cgbn_update_running_stats(const float* mean, const float* mean_lo, c
     return launched();
 }
 
-cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
-                         const float* gamma, const float* beta, float eps,
-                         void* y, float* mean, float* invstd,
-                         cgbn_dtype dtype, float* mean_lo,
+}  // extern "C"
+
+namespace {
+
+// Algorithm 1, optionally followed by "+ shortcut" and a ReLU (relu == true)
+cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, int C, int H, int W,
+                         cgbn_layout layout, int K, const float* gamma, const float* beta, float eps,
+                         void* y, float* mean, float* invstd, cgbn_dtype dtype, float* mean_lo,
                          void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!x || !gamma || !beta || !y || !mean || !invstd) return CGBN_ERR_NULL;
     Plan p;
     CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
     if (!eps_ok(eps)) return CGBN_ERR_EPS;
-    if (!aligned16(x) || !aligned16(y)) return CGBN_ERR_ALIGN;
+    if (!aligned16(x) || !aligned16(y) || !aligned16(shortcut)) return CGBN_ERR_ALIGN;
     CGBN_TRY(check_ws(p, workspace, workspace_bytes));
     char* ws = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -656,7 +664,7 @@ cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout 
     float* mlo = reinterpret_cast<float*>(ws + p.off_mlo);
     const int rev = (int)g_tune.reverse;
 
-    if (g_tune.fused && p.ff.ok) {
+    if (g_tune.fused && p.ff.ok && !relu) {
         FusedArgs F = fused_args(p, p.ff, ws);
         F.x = x; F.out = y; F.gamma = gamma; F.beta = beta; F.eps = (double)eps;
         F.mean = mean; F.mean_lo = mlo; F.mean_lo_user = mean_lo; F.invstd = invstd;
@@ -680,25 +688,30 @@ cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout 
     CGBN_TRY(launch_combine(CM_INVSTD, p, ws, invstd, nullptr, nullptr, sh0, nullptr, (double)eps, nullptr, st));
     // step 11
     A.invstd = invstd; A.gamma = gamma; A.beta = beta; A.out = y; A.reverse = 0;
-    return launch_map(EL_NORM, p, A, st);
+    A.dy = shortcut;
+    return launch_map(!relu ? EL_NORM : shortcut ? EL_NORM_ADD_RELU : EL_NORM_RELU, p, A, st);
 }
 
-cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, const float* invstd,
-                          const float* gamma, void* dx, float* dgamma, float* dbeta,
+// The backward; with `y` (the stored output of the ReLU variant) dy is first masked by y > 0
+// and `dshortcut`, if not null, receives the masked dy.
+cgbn_status backward_impl(const void* dy, const void* y, const void* x, const float* mean, const float* invstd,
+                          const float* gamma, void* dx, void* dshortcut, float* dgamma, float* dbeta,
                           int N, int C, int H, int W, cgbn_layout layout, int K,
                           cgbn_dtype dtype, const float* mean_lo,
                           void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!dy || !x || !mean || !invstd || !gamma || !dx || !dgamma || !dbeta) return CGBN_ERR_NULL;
+    const bool relu = y != nullptr;
     Plan p;
     CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
-    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx)) return CGBN_ERR_ALIGN;
+    if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(y) || !aligned16(dshortcut)) return CGBN_ERR_ALIGN;
+    if (dshortcut && dshortcut == dx) return CGBN_ERR_NULL;
     CGBN_TRY(check_ws(p, workspace, workspace_bytes));
     char* ws = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int rev = (int)g_tune.reverse;
 
-    if (g_tune.fused && p.fb.ok) {
+    if (g_tune.fused && p.fb.ok && !relu) {
         FusedArgs F = fused_args(p, p.fb, ws);
         F.x = x; F.dy = dy; F.out = dx; F.gamma = gamma;
         F.mean = const_cast<float*>(mean); F.mean_lo = const_cast<float*>(mean_lo);
@@ -717,12 +730,57 @@ cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, cons
     A.part0 = reinterpret_cast<float*>(ws + p.off_part0);
     A.part1 = reinterpret_cast<float*>(ws + p.off_part1);
     A.reverse = rev;
-    CGBN_TRY(launch_reduce(OP_BWD, p, A, st));
+    A.aux = y; A.out2 = dshortcut;
+    CGBN_TRY(launch_reduce(relu ? OP_BWD_RELU : OP_BWD, p, A, st));
     CGBN_TRY(launch_combine(CM_BWD, p, ws, dbeta, dgamma, nullptr,
                             reinterpret_cast<double*>(ws + p.off_sh0), reinterpret_cast<double*>(ws + p.off_sh1),
                             0.0, nullptr, st));
     A.gamma = gamma; A.dgamma = dgamma; A.dbeta = dbeta; A.out = dx; A.reverse = 0;
-    return launch_map(EL_DX, p, A, st);
+    return launch_map(relu ? EL_DX_RELU : EL_DX, p, A, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                         const float* gamma, const float* beta, float eps,
+                         void* y, float* mean, float* invstd,
+                         cgbn_dtype dtype, float* mean_lo,
+                         void* workspace, size_t workspace_bytes, void* stream)
+{
+    return forward_impl(x, nullptr, false, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, dtype, mean_lo,
+                        workspace, workspace_bytes, stream);
+}
+
+cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, const float* invstd,
+                          const float* gamma, void* dx, float* dgamma, float* dbeta,
+                          int N, int C, int H, int W, cgbn_layout layout, int K,
+                          cgbn_dtype dtype, const float* mean_lo,
+                          void* workspace, size_t workspace_bytes, void* stream)
+{
+    return backward_impl(dy, nullptr, x, mean, invstd, gamma, dx, nullptr, dgamma, dbeta, N, C, H, W, layout, K,
+                         dtype, mean_lo, workspace, workspace_bytes, stream);
+}
+
+cgbn_status cgbn_forward_relu(const void* x, const void* shortcut, int N, int C, int H, int W,
+                              cgbn_layout layout, int K, const float* gamma, const float* beta, float eps,
+                              void* y, float* mean, float* invstd, cgbn_dtype dtype, float* mean_lo,
+                              void* workspace, size_t workspace_bytes, void* stream)
+{
+    return forward_impl(x, shortcut, true, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, dtype, mean_lo,
+                        workspace, workspace_bytes, stream);
+}
+
+cgbn_status cgbn_backward_relu(const void* dy, const void* y, const void* x, const float* mean, const float* invstd,
+                               const float* gamma, void* dx, void* dshortcut, float* dgamma, float* dbeta,
+                               int N, int C, int H, int W, cgbn_layout layout, int K,
+                               cgbn_dtype dtype, const float* mean_lo,
+                               void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!y) return CGBN_ERR_NULL;
+    return backward_impl(dy, y, x, mean, invstd, gamma, dx, dshortcut, dgamma, dbeta, N, C, H, W, layout, K,
+                         dtype, mean_lo, workspace, workspace_bytes, stream);
 }
 
 const char* cgbn_status_string(cgbn_status status)

@@ -8,6 +8,10 @@
 //   reduce  OP_BWD    sum dy, sum dy*xhat         backward device sums
 //   map     EL_NORM   y  = gamma*(x-mean)*invstd + beta            step 11
 //   map     EL_DX     dx = gamma*invstd*(dy - dbeta/M - xhat*dgamma/M)
+//   reduce  OP_BWD_RELU       the same sums of dz = dy where y > 0 (y: the stored output)
+//   map     EL_NORM_RELU      y  = max(0, step 11)
+//   map     EL_NORM_ADD_RELU  y  = max(0, step 11 + shortcut)
+//   map     EL_DX_RELU        dx from dz; optionally writes dz, the shortcut's gradient
 //   map     EL_FROZEN y  = gamma*(x-m)/sqrt(s2+eps) + beta   fixed statistics m, s2 (sections 3.1, 3.3)
 //   map     EL_SCALE  dx = dy*gamma/sqrt(s2+eps)             backward of the fixed-statistics layer
 // A reduce sweep leaves one float per (channel, row) in `part`, where the rows
@@ -24,8 +28,15 @@ namespace cgbn {
 constexpr int kThreads = 256;   // 4 wavefronts per workgroup
 constexpr int kWave = 64;
 
-enum { OP_SUM = 0, OP_SQDEV = 1, OP_BWD = 2 };
-enum { EL_NORM = 0, EL_DX = 1, EL_FROZEN = 2, EL_SCALE = 3 };
+enum { OP_SUM = 0, OP_SQDEV = 1, OP_BWD = 2, OP_BWD_RELU = 3 };
+enum { EL_NORM = 0, EL_DX = 1, EL_FROZEN = 2, EL_SCALE = 3, EL_NORM_RELU = 4, EL_NORM_ADD_RELU = 5, EL_DX_RELU = 6 };
+// which tensors a sweep reads besides x: `dy` (the second input: dy, or the shortcut) and
+// `aux` (the third: the stored output y, whose sign is the ReLU's mask)
+constexpr bool op_has_dy(int op) { return op == OP_BWD || op == OP_BWD_RELU; }
+constexpr bool op_has_y(int op) { return op == OP_BWD_RELU; }
+constexpr bool el_has_2(int el) { return el == EL_DX || el == EL_NORM_ADD_RELU || el == EL_DX_RELU; }
+constexpr bool el_has_3(int el) { return el == EL_DX_RELU; }
+constexpr bool el_is_norm(int el) { return el == EL_NORM || el == EL_NORM_RELU || el == EL_NORM_ADD_RELU; }
 enum { CM_MEAN = 0, CM_INVSTD = 1, CM_BWD = 2, CM_SHARDS1 = 3, CM_SHARDS2 = 4 };
 
 struct bf16_t { uint16_t bits; };
@@ -36,7 +47,9 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 struct SweepArgs {
     const void* x;
     const void* dy;
+    const void* aux;          // stored output y (ReLU variants of the backward)
     void* out;
+    void* out2;               // dz, the shortcut's gradient (EL_DX_RELU; may be null)
     const float* mean;
     const float* mean_lo;     // may be null
     const float* invstd;
@@ -204,7 +217,7 @@ template <typename T, int OP> __device__ __forceinline__ ChanConst reduce_consts
         k.mu = A.mean[c];
         k.mulo = A.mean_lo ? A.mean_lo[c] : 0.f;
     }
-    if (OP == OP_BWD) k.istd = A.invstd[c];
+    if (op_has_dy(OP)) k.istd = A.invstd[c];
     return k;
 }
 
@@ -226,7 +239,7 @@ template <int EL> __device__ __forceinline__ ChanConst map_consts(const SweepArg
     k.mulo = A.mean_lo ? A.mean_lo[c] : 0.f;
     k.istd = A.invstd[c];
     k.g = A.gamma[c] * k.istd;
-    if (EL == EL_NORM) {
+    if (el_is_norm(EL)) {
         k.b = A.beta[c];
         k.c2 = 0.f;
     } else {
@@ -236,8 +249,9 @@ template <int EL> __device__ __forceinline__ ChanConst map_consts(const SweepArg
     return k;
 }
 
-template <int OP> __device__ __forceinline__ void accumulate(const ChanConst& k, float xv, float dyv, float& a0, float& a1)
+template <int OP> __device__ __forceinline__ void accumulate(const ChanConst& k, float xv, float dyv, float yv, float& a0, float& a1)
 {
+    if (op_has_y(OP)) dyv = yv > 0.f ? dyv : 0.f;
     if (OP == OP_SUM) {
         a0 += xv - k.mu;
     } else if (OP == OP_SQDEV) {
@@ -250,12 +264,23 @@ template <int OP> __device__ __forceinline__ void accumulate(const ChanConst& k,
     }
 }
 
-template <int EL> __device__ __forceinline__ float map_value(const ChanConst& k, float xv, float dyv)
+// `v2`: dy or the shortcut; `v3`: the stored output; `dz`: the masked dy (EL_DX_RELU)
+template <int EL> __device__ __forceinline__ float map_value(const ChanConst& k, float xv, float v2, float v3, float& dz)
 {
     if (EL == EL_SCALE) return xv * k.g;
     if (EL == EL_FROZEN) return (xv - k.mu) * k.g + k.b;
     float d = (xv - k.mu) - k.mulo;
     if (EL == EL_NORM) return d * k.g + k.b;
+    if (EL == EL_NORM_RELU || EL == EL_NORM_ADD_RELU) {
+        float z = d * k.g + k.b;
+        if (EL == EL_NORM_ADD_RELU) z += v2;
+        return z < 0.f ? 0.f : z;                  // NaN stays NaN
+    }
+    float dyv = v2;
+    if (EL == EL_DX_RELU) {
+        dyv = v3 > 0.f ? v2 : 0.f;
+        dz = dyv;
+    }
     return k.g * ((dyv - k.b) - (d * k.istd) * k.c2);
 }
 
@@ -265,80 +290,107 @@ template <int EL> __device__ __forceinline__ float map_value(const ChanConst& k,
 
 template <typename T, int OP> struct PlaneReduce {
     static constexpr int VEC = Elem<T>::VEC;
+    static constexpr bool DY = op_has_dy(OP), Y = op_has_y(OP);
     const T* x;
     const T* dy;
+    const T* aux;
     ChanConst k;
     float a0[VEC], a1[VEC];
 
     __device__ __forceinline__ void one(long long off)
     {
         float xv = Elem<T>::load1(x + off);
-        float dv = OP == OP_BWD ? Elem<T>::load1(dy + off) : 0.f;
-        accumulate<OP>(k, xv, dv, a0[0], a1[0]);
+        float dv = DY ? Elem<T>::load1(dy + off) : 0.f;
+        float yv = Y ? Elem<T>::load1(aux + off) : 0.f;
+        accumulate<OP>(k, xv, dv, yv, a0[0], a1[0]);
     }
     __device__ __forceinline__ void vec(long long off)
     {
-        float xv[VEC], dv[VEC];
+        float xv[VEC], dv[VEC], yv[VEC];
         Elem<T>::loadv(x + off, xv);
-        if (OP == OP_BWD) Elem<T>::loadv(dy + off, dv);
+        if (DY) Elem<T>::loadv(dy + off, dv);
+        if (Y) Elem<T>::loadv(aux + off, yv);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) accumulate<OP>(k, xv[e], OP == OP_BWD ? dv[e] : 0.f, a0[e], a1[e]);
+        for (int e = 0; e < VEC; ++e) accumulate<OP>(k, xv[e], DY ? dv[e] : 0.f, Y ? yv[e] : 0.f, a0[e], a1[e]);
     }
     __device__ __forceinline__ void four(long long off, long long step)
     {
-        float xv[4][VEC], dv[4][VEC];
+        float xv[4][VEC], dv[4][VEC], yv[4][VEC];
 #pragma unroll
         for (int u = 0; u < 4; ++u) Elem<T>::loadv(x + off + u * step, xv[u]);
-        if (OP == OP_BWD) {
+        if (DY) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) Elem<T>::loadv(dy + off + u * step, dv[u]);
+        }
+        if (Y) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Elem<T>::loadv(aux + off + u * step, yv[u]);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
 #pragma unroll
             for (int e = 0; e < VEC; ++e)
-                accumulate<OP>(k, xv[u][e], OP == OP_BWD ? dv[u][e] : 0.f, a0[e], a1[e]);
+                accumulate<OP>(k, xv[u][e], DY ? dv[u][e] : 0.f, Y ? yv[u][e] : 0.f, a0[e], a1[e]);
     }
 };
 
 template <typename T, int EL> struct PlaneMap {
     static constexpr int VEC = Elem<T>::VEC;
+    static constexpr bool IN2 = el_has_2(EL), IN3 = el_has_3(EL);
     const T* x;
     const T* dy;
+    const T* aux;
     T* out;
+    T* out2;       // may be null
     ChanConst k;
     int nt;
 
     __device__ __forceinline__ void one(long long off)
     {
         float xv = Elem<T>::load1(x + off);
-        float dv = EL == EL_DX ? Elem<T>::load1(dy + off) : 0.f;
-        Elem<T>::store1(out + off, map_value<EL>(k, xv, dv));
+        float v2 = IN2 ? Elem<T>::load1(dy + off) : 0.f;
+        float v3 = IN3 ? Elem<T>::load1(aux + off) : 0.f;
+        float dz = 0.f;
+        Elem<T>::store1(out + off, map_value<EL>(k, xv, v2, v3, dz));
+        if (IN3 && out2) Elem<T>::store1(out2 + off, dz);
     }
     __device__ __forceinline__ void vec(long long off)
     {
-        float xv[VEC], dv[VEC], r[VEC];
+        float xv[VEC], v2[VEC], v3[VEC], r[VEC], dz[VEC];
         Elem<T>::loadv(x + off, xv);
-        if (EL == EL_DX) Elem<T>::loadv(dy + off, dv);
+        if (IN2) Elem<T>::loadv(dy + off, v2);
+        if (IN3) Elem<T>::loadv(aux + off, v3);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) r[e] = map_value<EL>(k, xv[e], EL == EL_DX ? dv[e] : 0.f);
+        for (int e = 0; e < VEC; ++e) {
+            dz[e] = 0.f;
+            r[e] = map_value<EL>(k, xv[e], IN2 ? v2[e] : 0.f, IN3 ? v3[e] : 0.f, dz[e]);
+        }
         Elem<T>::storev(out + off, r, nt);
+        if (IN3 && out2) Elem<T>::storev(out2 + off, dz, nt);
     }
     __device__ __forceinline__ void four(long long off, long long step)
     {
-        float xv[4][VEC], dv[4][VEC];
+        float xv[4][VEC], v2[4][VEC], v3[4][VEC];
 #pragma unroll
         for (int u = 0; u < 4; ++u) Elem<T>::loadv(x + off + u * step, xv[u]);
-        if (EL == EL_DX) {
+        if (IN2) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) Elem<T>::loadv(dy + off + u * step, dv[u]);
+            for (int u = 0; u < 4; ++u) Elem<T>::loadv(dy + off + u * step, v2[u]);
+        }
+        if (IN3) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Elem<T>::loadv(aux + off + u * step, v3[u]);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            float r[VEC];
+            float r[VEC], dz[VEC];
 #pragma unroll
-            for (int e = 0; e < VEC; ++e) r[e] = map_value<EL>(k, xv[u][e], EL == EL_DX ? dv[u][e] : 0.f);
+            for (int e = 0; e < VEC; ++e) {
+                dz[e] = 0.f;
+                r[e] = map_value<EL>(k, xv[u][e], IN2 ? v2[u][e] : 0.f, IN3 ? v3[u][e] : 0.f, dz[e]);
+            }
             Elem<T>::storev(out + off + u * step, r, nt);
+            if (IN3 && out2) Elem<T>::storev(out2 + off + u * step, dz, nt);
         }
     }
 };
@@ -348,7 +400,7 @@ template <typename T, int OP>
 __global__ __launch_bounds__(kThreads) void nchw_reduce_block(SweepArgs A)
 {
     constexpr int VEC = Elem<T>::VEC;
-    constexpr int Q = OP == OP_BWD ? 2 : 1;
+    constexpr int Q = op_has_dy(OP) ? 2 : 1;
     __shared__ float sm[2 * 4];
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int j = (int)(b % A.sp);
@@ -361,6 +413,7 @@ __global__ __launch_bounds__(kThreads) void nchw_reduce_block(SweepArgs A)
     PlaneReduce<T, OP> f;
     f.x = static_cast<const T*>(A.x);
     f.dy = static_cast<const T*>(A.dy);
+    f.aux = static_cast<const T*>(A.aux);
     f.k = reduce_consts<T, OP>(A, c);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { f.a0[e] = 0.f; f.a1[e] = 0.f; }
@@ -382,7 +435,7 @@ template <typename T, int OP>
 __global__ __launch_bounds__(kThreads) void nchw_reduce_wave(SweepArgs A)
 {
     constexpr int VEC = Elem<T>::VEC;
-    constexpr int Q = OP == OP_BWD ? 2 : 1;
+    constexpr int Q = op_has_dy(OP) ? 2 : 1;
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
     long long plane = b * 4 + w;
@@ -393,6 +446,7 @@ __global__ __launch_bounds__(kThreads) void nchw_reduce_wave(SweepArgs A)
     PlaneReduce<T, OP> f;
     f.x = static_cast<const T*>(A.x);
     f.dy = static_cast<const T*>(A.dy);
+    f.aux = static_cast<const T*>(A.aux);
     f.k = reduce_consts<T, OP>(A, c);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { f.a0[e] = 0.f; f.a1[e] = 0.f; }
@@ -420,7 +474,9 @@ __global__ __launch_bounds__(kThreads) void nchw_map_block(SweepArgs A)
     PlaneMap<T, EL> f;
     f.x = static_cast<const T*>(A.x);
     f.dy = static_cast<const T*>(A.dy);
+    f.aux = static_cast<const T*>(A.aux);
     f.out = static_cast<T*>(A.out);
+    f.out2 = static_cast<T*>(A.out2);
     f.k = map_consts<EL>(A, c);
     f.nt = A.nt;
     walk_segment<kThreads, VEC>(plane * A.HW + beg, len, (int)threadIdx.x, A.S, f);
@@ -438,7 +494,9 @@ __global__ __launch_bounds__(kThreads) void nchw_map_wave(SweepArgs A)
     PlaneMap<T, EL> f;
     f.x = static_cast<const T*>(A.x);
     f.dy = static_cast<const T*>(A.dy);
+    f.aux = static_cast<const T*>(A.aux);
     f.out = static_cast<T*>(A.out);
+    f.out2 = static_cast<T*>(A.out2);
     f.k = map_consts<EL>(A, c);
     f.nt = A.nt;
     walk_segment<kWave, VEC>(plane * A.HW, A.HW, lane, A.S, f);
@@ -454,7 +512,7 @@ __global__ __launch_bounds__(kThreads) void nchw_map_wave(SweepArgs A)
 template <typename T, int V, int OP>
 __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
 {
-    constexpr int Q = OP == OP_BWD ? 2 : 1;
+    constexpr int Q = op_has_dy(OP) ? 2 : 1;
     __shared__ float sm[Q * kThreads * V];
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int ct = (int)(b % A.ctiles);
@@ -479,30 +537,37 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
         for (int e = 0; e < V; ++e) kc[e] = reduce_consts<T, OP>(A, cb + e);
         const T* px = static_cast<const T*>(A.x) + pix0 * A.C + cb;
         const T* pd = static_cast<const T*>(A.dy) + pix0 * A.C + cb;
+        const T* py = static_cast<const T*>(A.aux) + pix0 * A.C + cb;
         const long long C = A.C;
         const int rpp = A.rpp;
         int i = r;
-        constexpr int UNR = OP == OP_BWD ? 4 : 8;        // loads in flight per lane and tensor
+        constexpr bool DY = op_has_dy(OP), Y = op_has_y(OP);
+        constexpr int UNR = DY ? 4 : 8;        // loads in flight per lane and tensor
         for (; i + (UNR - 1) * rpp < npix; i += UNR * rpp) {
-            float xv[UNR][V], dv[UNR][V];
+            float xv[UNR][V], dv[UNR][V], yv[UNR][V];
 #pragma unroll
             for (int u = 0; u < UNR; ++u) Access<T, V>::load(px + (long long)(i + u * rpp) * C, xv[u]);
-            if (OP == OP_BWD) {
+            if (DY) {
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, dv[u]);
+            }
+            if (Y) {
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) Access<T, V>::load(py + (long long)(i + u * rpp) * C, yv[u]);
             }
 #pragma unroll
             for (int u = 0; u < UNR; ++u)
 #pragma unroll
                 for (int e = 0; e < V; ++e)
-                    accumulate<OP>(kc[e], xv[u][e], OP == OP_BWD ? dv[u][e] : 0.f, a0[e], a1[e]);
+                    accumulate<OP>(kc[e], xv[u][e], DY ? dv[u][e] : 0.f, Y ? yv[u][e] : 0.f, a0[e], a1[e]);
         }
         for (; i < npix; i += rpp) {
-            float xv[V], dv[V];
+            float xv[V], dv[V], yv[V];
             Access<T, V>::load(px + (long long)i * C, xv);
-            if (OP == OP_BWD) Access<T, V>::load(pd + (long long)i * C, dv);
+            if (DY) Access<T, V>::load(pd + (long long)i * C, dv);
+            if (Y) Access<T, V>::load(py + (long long)i * C, yv);
 #pragma unroll
-            for (int e = 0; e < V; ++e) accumulate<OP>(kc[e], xv[e], OP == OP_BWD ? dv[e] : 0.f, a0[e], a1[e]);
+            for (int e = 0; e < V; ++e) accumulate<OP>(kc[e], xv[e], DY ? dv[e] : 0.f, Y ? yv[e] : 0.f, a0[e], a1[e]);
         }
     }
     // fold the rpp pixel rows of the workgroup, in a fixed order
@@ -550,33 +615,49 @@ __global__ __launch_bounds__(kThreads) void nhwc_map(SweepArgs A)
     for (int e = 0; e < V; ++e) kc[e] = map_consts<EL>(A, cb + e);
     const T* px = static_cast<const T*>(A.x) + pix0 * A.C + cb;
     const T* pd = static_cast<const T*>(A.dy) + pix0 * A.C + cb;
+    const T* py = static_cast<const T*>(A.aux) + pix0 * A.C + cb;
     T* po = static_cast<T*>(A.out) + pix0 * A.C + cb;
+    T* po2 = A.out2 ? static_cast<T*>(A.out2) + pix0 * A.C + cb : nullptr;
+    constexpr bool IN2 = el_has_2(EL), IN3 = el_has_3(EL);
     const long long C = A.C;
     const int rpp = A.rpp;
     int i = r;
     for (; i + 3 * rpp < npix; i += 4 * rpp) {
-        float xv[4][V], dv[4][V];
+        float xv[4][V], v2[4][V], v3[4][V];
 #pragma unroll
         for (int u = 0; u < 4; ++u) Access<T, V>::load(px + (long long)(i + u * rpp) * C, xv[u]);
-        if (EL == EL_DX) {
+        if (IN2) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, dv[u]);
+            for (int u = 0; u < 4; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, v2[u]);
+        }
+        if (IN3) {
+#pragma unroll
+            for (int u = 0; u < 4; ++u) Access<T, V>::load(py + (long long)(i + u * rpp) * C, v3[u]);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            float o[V];
+            float o[V], dz[V];
 #pragma unroll
-            for (int e = 0; e < V; ++e) o[e] = map_value<EL>(kc[e], xv[u][e], EL == EL_DX ? dv[u][e] : 0.f);
+            for (int e = 0; e < V; ++e) {
+                dz[e] = 0.f;
+                o[e] = map_value<EL>(kc[e], xv[u][e], IN2 ? v2[u][e] : 0.f, IN3 ? v3[u][e] : 0.f, dz[e]);
+            }
             Access<T, V>::store(po + (long long)(i + u * rpp) * C, o, A.nt);
+            if (IN3 && po2) Access<T, V>::store(po2 + (long long)(i + u * rpp) * C, dz, A.nt);
         }
     }
     for (; i < npix; i += rpp) {
-        float xv[V], dv[V], o[V];
+        float xv[V], v2[V], v3[V], o[V], dz[V];
         Access<T, V>::load(px + (long long)i * C, xv);
-        if (EL == EL_DX) Access<T, V>::load(pd + (long long)i * C, dv);
+        if (IN2) Access<T, V>::load(pd + (long long)i * C, v2);
+        if (IN3) Access<T, V>::load(py + (long long)i * C, v3);
 #pragma unroll
-        for (int e = 0; e < V; ++e) o[e] = map_value<EL>(kc[e], xv[e], EL == EL_DX ? dv[e] : 0.f);
+        for (int e = 0; e < V; ++e) {
+            dz[e] = 0.f;
+            o[e] = map_value<EL>(kc[e], xv[e], IN2 ? v2[e] : 0.f, IN3 ? v3[e] : 0.f, dz[e]);
+        }
         Access<T, V>::store(po + (long long)i * C, o, A.nt);
+        if (IN3 && po2) Access<T, V>::store(po2 + (long long)i * C, dz, A.nt);
     }
 }
 

@@ -278,6 +278,24 @@ def main():
         ms = statistics.mean(time_calls(torch, fn, 3, max(10, args.steps // 2)))
         frozen[name] = dict(ms=ms, GBps=2 * Sb / ms / 1e6, frac_of_peak=2 * Sb / ms / 1e6 / PEAK_GBPS)
 
+    # CGBN + shortcut add + ReLU on the same tensors (y doubles as the stored output the backward masks by)
+    relu = {}
+    shortcut = layer.dy                                              # any tensor of the right shape
+    dz = torch.empty_like(layer.x)
+    for name, sc, dsc in (("relu", None, None), ("add_relu", shortcut, dz)):
+        fw = lambda: cgbn.cgbn_forward_relu(layer.x, sc, *layer.shape, wl.layout, wl.K, layer.gamma, layer.beta, wl.eps,
+                                            layer.y, layer.mean, layer.invstd, wl.dtype, layer.mean_lo, layer.ws)
+        bw = lambda: cgbn.cgbn_backward_relu(layer.dy, layer.y, layer.x, layer.mean, layer.invstd, layer.gamma, layer.dx,
+                                             dsc, layer.dgamma, layer.dbeta, *layer.shape, wl.layout, wl.K, wl.dtype,
+                                             layer.mean_lo, layer.ws)
+        fms = statistics.median(time_calls(torch, fw, 3, max(10, args.steps // 2)))
+        bms = statistics.median(time_calls(torch, bw, 3, max(10, args.steps // 2)))
+        moved_f, moved_b = (3 if sc is not None else 2), (5 if dsc is not None else 4)
+        relu[name] = dict(fwd_ms=fms, bwd_ms=bms, fwd_moved_GBps=moved_f * Sb / fms / 1e6, bwd_moved_GBps=moved_b * Sb / bms / 1e6,
+                          single_launch=dict(forward=cgbn.cgbn_get_tuning("last_forward_fused"),
+                                             backward=cgbn.cgbn_get_tuning("last_backward_fused")))
+    del dz
+
     if args.calibrate:
         nb = 1 << 30
         a, b = torch.empty(nb, dtype=torch.uint8, device=dev), torch.empty(nb, dtype=torch.uint8, device=dev)
@@ -321,7 +339,7 @@ def main():
         "pct_of_peak": head["pct_of_peak"], "fwd_ms": head["fwd_ms"], "bwd_ms": head["bwd_ms"],
         "floor_GBps": head["floor_GBps"],
         "step_ms": {"median": head["step_ms_median"], "min": head["step_ms_min"], "max": head["step_ms_max"]},
-        "sweeps": sweeps, "fixed_statistics_mode": frozen, "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,
+        "sweeps": sweeps, "fixed_statistics_mode": frozen, "relu_variants": relu, "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,
         "device": torch.cuda.get_device_name(0), "hip": torch.version.hip,
         "compute_units": torch.cuda.get_device_properties(0).multi_processor_count,
     }

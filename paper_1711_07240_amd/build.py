@@ -1,28 +1,61 @@
-"""Build libcgbn.so for gfx950 in-tree with hipcc (cross-compiles without a GPU)."""
+"""Build libcgbn.so for gfx950 in-tree with hipcc (cross-compiles without a GPU).
+
+The host code and the multi-sweep kernels are one translation unit; the NCHW
+single-launch kernels are instantiated in eight more (element type x direction
+x activation), compiled side by side, then everything is linked into one
+shared library."""
 
 from __future__ import annotations
 
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libcgbn.so")
-SOURCES = [os.path.join(PKG, "csrc", "cgbn.hip")]
+CSRC = os.path.join(PKG, "csrc")
+OBJ = os.path.join(PKG, "_build")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 FLAGS = [
-    "-O3", "-std=c++17", "--offload-arch=gfx950", "-shared", "-fPIC",
+    "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fno-gpu-rdc", "-Wall", "-Wno-unused-function",
-    "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
+    "-I", os.path.join(ROOT, "include"), "-I", CSRC,
 ]
 
 
-def build(verbose: bool = True) -> str:
-    cmd = [HIPCC] + FLAGS + ["-o", LIB] + SOURCES
+def _units():
+    """(object file, source, extra flags) of every translation unit."""
+    units = [(os.path.join(OBJ, "cgbn.o"), os.path.join(CSRC, "cgbn.hip"), [])]
+    for tname, t in (("f32", "float"), ("bf16", "bf16_t")):
+        for fwd in (1, 0):
+            for act in (0, 1):
+                obj = os.path.join(OBJ, f"fused_{tname}_{'fwd' if fwd else 'bwd'}_act{act}.o")
+                units.append((obj, os.path.join(CSRC, "cgbn_fused_inst.hip"),
+                              [f"-DCGBN_INST_T={t}", f"-DCGBN_INST_FWD={fwd}", f"-DCGBN_INST_ACT={act}"]))
+    return units
+
+
+def build(verbose: bool = True, jobs: int | None = None) -> str:
+    os.makedirs(OBJ, exist_ok=True)
+    units = _units()
+    jobs = jobs or max(1, min(len(units), int(os.environ.get("MAX_JOBS", os.cpu_count() or 1)), 16))
+
+    def compile_one(u):
+        obj, src, extra = u
+        cmd = [HIPCC] + FLAGS + extra + ["-c", src, "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=jobs) as ex:
+        objs = list(ex.map(compile_one, units))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-fno-gpu-rdc", "-shared", "-fPIC", "-o", LIB] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

@@ -5,9 +5,34 @@
 #include "cgbn_kernels.h"
 #include "cgbn_fused.h"
 #include "cgbn_fused_nhwc.h"
+#include "cgbn_fused_list.h"
 
 #include <cmath>
 #include <cstring>
+#include <map>
+#include <mutex>
+#include <utility>
+
+// The NCHW single-launch kernels are instantiated in cgbn_fused_inst.hip (one translation
+// unit per element type, direction and activation); here they are only declared.
+namespace cgbn {
+#define CGBN_DECL_F(LB_, LPPC_)                                                               \
+    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 0>(FusedArgs);     \
+    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 1>(FusedArgs);     \
+    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 0>(FusedArgs);    \
+    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 1>(FusedArgs);
+#define CGBN_DECL_B(LB_, LPPC_)                                                               \
+    extern template __global__ void nchw_fused_backward<float, LB_, LPPC_, 0>(FusedArgs);    \
+    extern template __global__ void nchw_fused_backward<float, LB_, LPPC_, 1>(FusedArgs);    \
+    extern template __global__ void nchw_fused_backward<bf16_t, LB_, LPPC_, 0>(FusedArgs);   \
+    extern template __global__ void nchw_fused_backward<bf16_t, LB_, LPPC_, 1>(FusedArgs);
+CGBN_FUSED_COMMON(CGBN_DECL_F)
+CGBN_FUSED_FORWARD_ONLY(CGBN_DECL_F)
+CGBN_FUSED_COMMON(CGBN_DECL_B)
+CGBN_FUSED_BACKWARD_ONLY(CGBN_DECL_B)
+#undef CGBN_DECL_F
+#undef CGBN_DECL_B
+}  // namespace cgbn
 
 namespace {
 
@@ -349,13 +374,20 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
 
 // ---- register-resident path ------------------------------------------------
 
+// workgroups of `kernel` that are resident at once on the current device (cached per kernel and device)
 template <typename KernelT> int resident_groups(KernelT kernel)
 {
-    // workgroups of `kernel` that are resident at once on the current device
+    static std::mutex lock;
+    static std::map<std::pair<const void*, int>, int> cache;
     int dev = 0, per_cu = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
+    const std::pair<const void*, int> key(reinterpret_cast<const void*>(kernel), dev);
+    std::lock_guard<std::mutex> hold(lock);
+    auto it = cache.find(key);
+    if (it != cache.end()) return it->second;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kThreads, 0) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    cache[key] = per_cu * cus;
     return per_cu * cus;
 }
 
@@ -363,11 +395,7 @@ template <typename KernelT>
 cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st,
                                 bool* taken)
 {
-    static int cached_dev = -1, cached_groups = 0;       // per kernel instantiation
-    int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return CGBN_ERR_HIP;
-    if (dev != cached_dev) { cached_groups = resident_groups(kernel); cached_dev = dev; }
-    long long groups = cached_groups;
+    long long groups = resident_groups(kernel);
     if (g_tune.fused_groups > 0 && g_tune.fused_groups < groups) groups = g_tune.fused_groups;
     if (groups > f.total_units) groups = f.total_units;
     *taken = false;
@@ -393,35 +421,29 @@ cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A
     return launched();
 }
 
-template <typename T, bool FWD>
+// ACT: the ReLU variants (NCHW only; channels-last shapes take the multi-sweep kernels then)
+template <typename T, bool FWD, int ACT>
 cgbn_status launch_fused_t(const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st, bool* taken)
 {
+    *taken = false;
     if (f.nhwc) {
         constexpr int LBn = 4 * (int)sizeof(T);
-        if constexpr (FWD) return launch_fused_kernel(nhwc_fused_forward<T, LBn>, f, A, sync_words, st, taken);
+        if constexpr (ACT != 0) return CGBN_OK;
+        else if constexpr (FWD) return launch_fused_kernel(nhwc_fused_forward<T, LBn>, f, A, sync_words, st, taken);
         else return launch_fused_kernel(nhwc_fused_backward<T, LBn>, f, A, sync_words, st, taken);
     }
 #define CGBN_FUSED_CASE(LB_, LPPC_)                                                                          \
     if (f.LB == LB_ && f.LPPC == LPPC_) {                                                                    \
-        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_>, f, A, sync_words, st, taken); \
-        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_>, f, A, sync_words, st, taken);    \
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT>, f, A, sync_words, st, taken); \
+        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT>, f, A, sync_words, st, taken); \
     }
-    // slot counts per plane with R/16 <= count <= R, R the register slots per tensor
-    // (forward: 32 for 16-byte loads, 64 for 8-byte; backward: 16 and 32)
-    CGBN_FUSED_CASE(16, 0) CGBN_FUSED_CASE(8, 0)
-    CGBN_FUSED_CASE(16, 2) CGBN_FUSED_CASE(16, 3) CGBN_FUSED_CASE(16, 4) CGBN_FUSED_CASE(16, 5)
-    CGBN_FUSED_CASE(16, 6) CGBN_FUSED_CASE(16, 8) CGBN_FUSED_CASE(16, 10) CGBN_FUSED_CASE(16, 12)
-    CGBN_FUSED_CASE(16, 16)
-    CGBN_FUSED_CASE(8, 4) CGBN_FUSED_CASE(8, 5) CGBN_FUSED_CASE(8, 6) CGBN_FUSED_CASE(8, 8)
-    CGBN_FUSED_CASE(8, 10) CGBN_FUSED_CASE(8, 12) CGBN_FUSED_CASE(8, 16) CGBN_FUSED_CASE(8, 24)
-    CGBN_FUSED_CASE(8, 32)
+    CGBN_FUSED_COMMON(CGBN_FUSED_CASE)
     if constexpr (FWD) {
-        CGBN_FUSED_CASE(16, 24) CGBN_FUSED_CASE(16, 32) CGBN_FUSED_CASE(8, 64)
+        CGBN_FUSED_FORWARD_ONLY(CGBN_FUSED_CASE)
     } else {
-        CGBN_FUSED_CASE(8, 2) CGBN_FUSED_CASE(8, 3)
+        CGBN_FUSED_BACKWARD_ONLY(CGBN_FUSED_CASE)
     }
 #undef CGBN_FUSED_CASE
-    *taken = false;
     return CGBN_OK;
 }
 
@@ -664,14 +686,17 @@ cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, 
     float* mlo = reinterpret_cast<float*>(ws + p.off_mlo);
     const int rev = (int)g_tune.reverse;
 
-    if (g_tune.fused && p.ff.ok && !relu) {
+    if (g_tune.fused && p.ff.ok) {
         FusedArgs F = fused_args(p, p.ff, ws);
-        F.x = x; F.out = y; F.gamma = gamma; F.beta = beta; F.eps = (double)eps;
+        F.x = x; F.out = y; F.gamma = gamma; F.beta = beta; F.eps = (double)eps; F.aux = shortcut;
         F.mean = mean; F.mean_lo = mlo; F.mean_lo_user = mean_lo; F.invstd = invstd;
         bool taken = false;
         const int sync_words = kSyncHeader + 8 * p.C;
-        cgbn_status st_ = p.dtype == CGBN_F32 ? launch_fused_t<float, true>(p.ff, F, sync_words, st, &taken)
-                                              : launch_fused_t<bf16_t, true>(p.ff, F, sync_words, st, &taken);
+        const bool f32 = p.dtype == CGBN_F32;
+        cgbn_status st_ = relu ? (f32 ? launch_fused_t<float, true, 1>(p.ff, F, sync_words, st, &taken)
+                                      : launch_fused_t<bf16_t, true, 1>(p.ff, F, sync_words, st, &taken))
+                               : (f32 ? launch_fused_t<float, true, 0>(p.ff, F, sync_words, st, &taken)
+                                      : launch_fused_t<bf16_t, true, 0>(p.ff, F, sync_words, st, &taken));
         g_last_forward_fused = taken;
         if (taken || st_ != CGBN_OK) return st_;
     }
@@ -711,15 +736,18 @@ cgbn_status backward_impl(const void* dy, const void* y, const void* x, const fl
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int rev = (int)g_tune.reverse;
 
-    if (g_tune.fused && p.fb.ok && !relu) {
+    if (g_tune.fused && p.fb.ok) {
         FusedArgs F = fused_args(p, p.fb, ws);
-        F.x = x; F.dy = dy; F.out = dx; F.gamma = gamma;
+        F.x = x; F.dy = dy; F.out = dx; F.gamma = gamma; F.aux = y; F.out2 = dshortcut;
         F.mean = const_cast<float*>(mean); F.mean_lo = const_cast<float*>(mean_lo);
         F.invstd = const_cast<float*>(invstd); F.dgamma = dgamma; F.dbeta = dbeta;
         bool taken = false;
         const int sync_words = kSyncHeader + 8 * p.C;
-        cgbn_status st_ = p.dtype == CGBN_F32 ? launch_fused_t<float, false>(p.fb, F, sync_words, st, &taken)
-                                              : launch_fused_t<bf16_t, false>(p.fb, F, sync_words, st, &taken);
+        const bool f32 = p.dtype == CGBN_F32;
+        cgbn_status st_ = relu ? (f32 ? launch_fused_t<float, false, 1>(p.fb, F, sync_words, st, &taken)
+                                      : launch_fused_t<bf16_t, false, 1>(p.fb, F, sync_words, st, &taken))
+                               : (f32 ? launch_fused_t<float, false, 0>(p.fb, F, sync_words, st, &taken)
+                                      : launch_fused_t<bf16_t, false, 0>(p.fb, F, sync_words, st, &taken));
         g_last_backward_fused = taken;
         if (taken || st_ != CGBN_OK) return st_;
     }

@@ -63,7 +63,9 @@ constexpr int kFusedMaxShards = 512;
 struct FusedArgs {
     const void* x;
     const void* dy;
+    const void* aux;      // ReLU variants: forward: the shortcut (may be null); backward: the stored output y
     void* out;
+    void* out2;           // ReLU variant of the backward: dz, the shortcut's gradient (may be null)
     const float* gamma;
     const float* beta;
     float* mean;          // forward: out; backward: in
@@ -101,7 +103,7 @@ struct FusedArgs {
 constexpr unsigned kRowSentinel = 0xffffffffu;
 
 // Before every launch: clear the error word and mark every row "not written yet".
-__global__ __launch_bounds__(kThreads) void fused_init(unsigned* sync, int sync_words, unsigned* rows, long long row_words)
+static __global__ __launch_bounds__(kThreads) void fused_init(unsigned* sync, int sync_words, unsigned* rows, long long row_words)
 {
     long long i = (long long)blockIdx.x * kThreads + threadIdx.x;
     for (long long j = i; j < sync_words; j += (long long)gridDim.x * kThreads) sync[j] = 0u;
@@ -154,6 +156,12 @@ __device__ __forceinline__ void lds_slot_read(const uint32_t* ext, int j, int t,
     out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
 }
 
+__device__ __forceinline__ void lds_slot_write(uint32_t* ext, int j, int t, const uint32_t* in)
+{
+    u32x4 v = {in[0], in[1], in[2], in[3]};
+    *reinterpret_cast<u32x4*>(ext + ((size_t)j * kThreads + t) * 4) = v;
+}
+
 // the elements packed in one 32-bit register
 template <typename T> struct Packed;
 template <> struct Packed<float> {
@@ -170,6 +178,19 @@ template <> struct Packed<bf16_t> {
     }
     static __device__ __forceinline__ uint32_t pack(const float (&f)[2]) { return f32_to_bf16(f[0]) | (f32_to_bf16(f[1]) << 16); }
 };
+
+// ReLU mask on packed words: keeps the elements of `g` whose partner in `y` is > 0
+template <typename T> __device__ __forceinline__ uint32_t mask_by_positive(uint32_t g, uint32_t y);
+template <> __device__ __forceinline__ uint32_t mask_by_positive<float>(uint32_t g, uint32_t y)
+{
+    return __uint_as_float(y) > 0.f ? g : 0u;
+}
+template <> __device__ __forceinline__ uint32_t mask_by_positive<bf16_t>(uint32_t g, uint32_t y)
+{
+    uint32_t lo = __uint_as_float(y << 16) > 0.f ? (g & 0x0000ffffu) : 0u;
+    uint32_t hi = __uint_as_float(y & 0xffff0000u) > 0.f ? (g & 0xffff0000u) : 0u;
+    return lo | hi;
+}
 
 // Rows move through agent-scope atomic loads and stores, which are coherent
 // across the chip's L2 slices by themselves.
@@ -393,7 +414,9 @@ struct Slots {
 // ---------------------------------------------------------------------------
 // forward: Algorithm 1 steps 1-11 in one launch
 // ---------------------------------------------------------------------------
-template <typename T, int LB, int LPPC>
+// ACT != 0: y = max(0, step 11 + shortcut), the shortcut (A.aux, may be null) being read
+// a few slots at a time while the unit is written out.
+template <typename T, int LB, int LPPC, int ACT>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 {
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
@@ -552,7 +575,49 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
         if (g.u == 0 && t == 0) A.invstd[c] = istd;
 
         // ---- step 11: normalise from registers, write y --------------------
-        {
+        if (ACT != 0 && A.aux != nullptr) {
+            // with a shortcut: its slots are fetched kBatch at a time, just before they are used
+            constexpr int kBatch = 8 / W;
+            const unsigned loff = SL::lane_offset(t);
+            const float gsc = A.gamma[c] * istd, bsh = A.beta[c];
+            const char* ru = static_cast<const char*>(A.aux) + g.base;
+#pragma unroll
+            for (int s0 = 0; s0 < RT; s0 += kBatch) {
+                uint32_t rw[kBatch][W];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const int s = s0 + j;
+                    if (s < RT && SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff))
+                        Words<LB>::load(ru + SL::plane_base(A, s, w) + SL::slot_offset(s) + loff, rw[j]);
+                }
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    const int s = s0 + j;
+                    if (s < RT && SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
+                        uint32_t o[W], wv[W];
+                        if (s < R) {
+#pragma unroll
+                            for (int q = 0; q < W; ++q) wv[q] = d[(s < R ? s : 0) * W + q];
+                        } else {
+                            lds_slot_read(ext, s - R, t, wv);
+                        }
+#pragma unroll
+                        for (int q = 0; q < W; ++q) {
+                            float f[EPW], r[EPW];
+                            Packed<T>::unpack(wv[q], f);
+                            Packed<T>::unpack(rw[j][q], r);
+#pragma unroll
+                            for (int e = 0; e < EPW; ++e) {
+                                float z = (((f[e] - mu) - mulo) * gsc + bsh) + r[e];
+                                f[e] = z < 0.f ? 0.f : z;
+                            }
+                            o[q] = Packed<T>::pack(f);
+                        }
+                        Words<LB>::store(yu + SL::plane_base(A, s, w) + SL::slot_offset(s) + loff, o, A.nt);
+                    }
+                }
+            }
+        } else {
             const unsigned loff = SL::lane_offset(t);
             const float gsc = A.gamma[c] * istd, bsh = A.beta[c];
 #pragma unroll
@@ -570,7 +635,10 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                         float f[EPW];
                         Packed<T>::unpack(wv[q], f);
 #pragma unroll
-                        for (int e = 0; e < EPW; ++e) f[e] = ((f[e] - mu) - mulo) * gsc + bsh;
+                        for (int e = 0; e < EPW; ++e) {
+                            f[e] = ((f[e] - mu) - mulo) * gsc + bsh;
+                            if (ACT != 0) f[e] = f[e] < 0.f ? 0.f : f[e];
+                        }
                         o[q] = Packed<T>::pack(f);
                     }
                     Words<LB>::store(yu + SL::plane_base(A, s, w) + SL::slot_offset(s) + loff, o, A.nt);
@@ -584,7 +652,10 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 // ---------------------------------------------------------------------------
 // backward: device sums, reduce, dx in one launch
 // ---------------------------------------------------------------------------
-template <typename T, int LB, int LPPC>
+// ACT != 0: dy is first masked by the stored output (A.aux) being positive.  The output's
+// slots pass through the storage that x takes afterwards, so the unit costs one more round
+// of loads but no more registers; the masked dy also goes to A.out2 if that is not null.
+template <typename T, int LB, int LPPC, int ACT>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
 {
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
@@ -614,7 +685,54 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
         const float istd = A.invstd[c];
         CGBN_STAMP(0);
 
-        {
+        if (ACT != 0) {
+            // round one: dy and the stored output y; mask dy; round two: x over y's storage
+            const char* yu = static_cast<const char*>(A.aux) + g.base;
+            const unsigned loff = SL::lane_offset(t);
+#pragma unroll
+            for (int s = 0; s < RT; ++s) {
+                if (SL::in_use(A, g, s, w)) {
+                    unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
+                    size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
+                    if (s < R) {
+                        Words<LB>::load(gu + o, &gd[(s < R ? s : 0) * W]);
+                        Words<LB>::load(yu + o, &xd[(s < R ? s : 0) * W]);
+                    } else {
+                        lds_slot_fill(gu + o, ext, s - R, w);
+                        lds_slot_fill(yu + o, ext, RL + s - R, w);
+                    }
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+            for (int s = 0; s < RT; ++s) {
+                if (SL::in_use(A, g, s, w)) {
+                    if (s < R) {
+#pragma unroll
+                        for (int q = 0; q < W; ++q)
+                            gd[(s < R ? s : 0) * W + q] = mask_by_positive<T>(gd[(s < R ? s : 0) * W + q], xd[(s < R ? s : 0) * W + q]);
+                    } else if (RL > 0) {
+                        uint32_t wg[4], wy[4];
+                        lds_slot_read(ext, s - R, t, wg);
+                        lds_slot_read(ext, RL + s - R, t, wy);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) wg[q] = mask_by_positive<T>(wg[q], wy[q]);
+                        lds_slot_write(ext, s - R, t, wg);
+                    }
+                }
+            }
+            // (a wavefront's LDS entries are its own: no barrier is needed before x lands on y's slots)
+#pragma unroll
+            for (int s = 0; s < RT; ++s) {
+                if (SL::in_use(A, g, s, w)) {
+                    unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
+                    size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
+                    if (s < R) Words<LB>::load(xu + o, &xd[(s < R ? s : 0) * W]);
+                    else lds_slot_fill(xu + o, ext, RL + s - R, w);
+                }
+            }
+            if (RL > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        } else {
             const unsigned loff = SL::lane_offset(t);
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
@@ -727,6 +845,9 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                         o[q] = Packed<T>::pack(fg);
                     }
                     Words<LB>::store(ou + SL::plane_base(A, s, w) + SL::slot_offset(s) + loff, o, A.nt);
+                    if (ACT != 0 && A.out2 != nullptr)
+                        Words<LB>::store(static_cast<char*>(A.out2) + g.base + SL::plane_base(A, s, w) + SL::slot_offset(s) + loff,
+                                         wg, A.nt);
                 }
             }
         }

@@ -1,0 +1,18 @@
+// Explicit instantiations of the NCHW single-launch kernels, one translation unit per
+// (element type, direction, activation) so that they compile side by side.  The build
+// passes CGBN_INST_T (float or bf16_t), CGBN_INST_FWD (0/1) and CGBN_INST_ACT (0/1).
+#include "cgbn_fused.h"
+#include "cgbn_fused_list.h"
+
+namespace cgbn {
+#if CGBN_INST_FWD
+#define CGBN_X(LB_, LPPC_) template __global__ void nchw_fused_forward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT>(FusedArgs);
+CGBN_FUSED_COMMON(CGBN_X)
+CGBN_FUSED_FORWARD_ONLY(CGBN_X)
+#else
+#define CGBN_X(LB_, LPPC_) template __global__ void nchw_fused_backward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT>(FusedArgs);
+CGBN_FUSED_COMMON(CGBN_X)
+CGBN_FUSED_BACKWARD_ONLY(CGBN_X)
+#endif
+#undef CGBN_X
+}  // namespace cgbn

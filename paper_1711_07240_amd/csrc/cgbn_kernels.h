@@ -784,7 +784,7 @@ __global__ __launch_bounds__(kThreads) void combine_shards(const double* s0, con
 // number of bytes, for calibrating hardware traffic counters.
 // Exponential moving average of the pooled statistics (one thread per channel, float64).
 // The biased batch variance is recovered from invstd: var = 1/invstd^2 - eps.
-__global__ __launch_bounds__(kThreads) void running_update(const float* mean, const float* mean_lo, const float* invstd,
+static __global__ __launch_bounds__(kThreads) void running_update(const float* mean, const float* mean_lo, const float* invstd,
                                                            double eps, double unbias, double momentum,
                                                            float* running_mean, float* running_var, int C)
 {
@@ -799,7 +799,7 @@ __global__ __launch_bounds__(kThreads) void running_update(const float* mean, co
     running_var[c] = (float)(keep * (double)running_var[c] + momentum * (var * unbias));
 }
 
-__global__ __launch_bounds__(kThreads) void calibration_copy(const u32x4* src, u32x4* dst, size_t nvec)
+static __global__ __launch_bounds__(kThreads) void calibration_copy(const u32x4* src, u32x4* dst, size_t nvec)
 {
     size_t i = (size_t)blockIdx.x * (kThreads * 8) + threadIdx.x;
 #pragma unroll

@@ -69,6 +69,11 @@ def _check(got, ref, dtype, what):
     return rep
 
 
+# shapes the single-launch kernels must take when they are switched on
+SINGLE_LAUNCH = {"nchw-f32-plane1050", "nchw-f32-plane600", "nchw-f32-plane40000", "nchw-f32-plane90000-two-tiles",
+                 "nchw-bf16-plane2600"}
+
+
 def run_relu_case(wl, what, with_shortcut):
     print(f"[case] relu {what} shortcut={with_shortcut}: N={wl.N} C={wl.C} H={wl.H} W={wl.W} {wl.layout} {wl.dtype} K={wl.K}",
           flush=True)
@@ -82,6 +87,9 @@ def run_relu_case(wl, what, with_shortcut):
     L.cgbn_backward_relu(p.dy, p.y, p.x, p.mean, p.invstd, p.gamma, p.dx, dz, p.dgamma, p.dbeta, *p.shape_args,
                          wl.layout, wl.K, wl.dtype, p.mean_lo, p.ws)
     got = p.results()
+    if what in SINGLE_LAUNCH:
+        want = L.cgbn_get_tuning("fused")
+        assert L.cgbn_get_tuning("last_forward_fused") == want and L.cgbn_get_tuning("last_backward_fused") == want
     if with_shortcut:
         got["dz"] = G.to_host_f64(dz, wl.dtype)
     xw, dyw = G.widen(d["x"], wl.dtype), G.widen(d["dy"], wl.dtype)
@@ -138,3 +146,51 @@ def test_relu_argument_errors():
         L.cgbn_backward_relu(p.dy, p.y, p.x, p.mean, p.invstd, p.gamma, p.dx, p.dx, p.dgamma, p.dbeta, *p.shape_args,
                              wl.layout, wl.K, wl.dtype, p.mean_lo, p.ws)
     assert e.value.code == 1
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg3"])
+def test_relu_full_size(name, path):
+    """The bench's launch configuration: sampled channels element by element against the oracle, every
+    channel's statistics and gradient sums against a float64 library reduction."""
+    if path == 0:
+        pytest.skip("the multi-sweep kernels at full size are covered by the plain CGBN tests; once is enough here")
+    wl = synth.WORKLOADS[name]
+    print(f"[case] relu full size {name}", flush=True)
+    gen = torch.Generator(device=G.DEV)
+    gen.manual_seed(wl.seed)
+    shape = (wl.N, wl.C, wl.H, wl.W)
+    mu, sigma, gamma, beta = (torch.from_numpy(a).to(G.DEV) for a in synth.channel_params(wl))
+    x = torch.randn(shape, generator=gen, device=G.DEV) * sigma.view(1, -1, 1, 1) + mu.view(1, -1, 1, 1)
+    sc = torch.randn(shape, generator=gen, device=G.DEV)
+    dy = torch.randn(shape, generator=gen, device=G.DEV) * wl.dy_sigma
+    y, dx, dz = torch.empty_like(x), torch.empty_like(x), torch.empty_like(x)
+    f = dict(dtype=torch.float32, device=G.DEV)
+    mean, invstd, mean_lo, dgamma, dbeta = (torch.empty(wl.C, **f) for _ in range(5))
+    ws = torch.empty(L.cgbn_workspace_bytes(*shape, wl.layout, wl.dtype, wl.K), dtype=torch.uint8, device=G.DEV)
+    L.cgbn_forward_relu(x, sc, *shape, wl.layout, wl.K, gamma, beta, wl.eps, y, mean, invstd, wl.dtype, mean_lo, ws)
+    L.cgbn_backward_relu(dy, y, x, mean, invstd, gamma, dx, dz, dgamma, dbeta, *shape, wl.layout, wl.K, wl.dtype,
+                         mean_lo, ws)
+    torch.cuda.synchronize()
+    assert L.cgbn_get_tuning("last_forward_fused") == 1 and L.cgbn_get_tuning("last_backward_fused") == 1
+    err = ws[L.cgbn_workspace_error_offset(*shape, wl.layout, wl.dtype, wl.K):][:4].view(torch.int32)
+    assert int(err.item()) == 0
+    # every channel: dz is a selection (bit-exact); gradient sums against float64 library reductions of dz
+    assert torch.equal(dz, torch.where(y > 0, dy, torch.zeros_like(dy)))
+    xh = (x.double() - (mean.double() + mean_lo.double()).view(1, -1, 1, 1)) * invstd.double().view(1, -1, 1, 1)
+    db64 = dz.double().sum(dim=(0, 2, 3))
+    dg64 = (dz.double() * xh).sum(dim=(0, 2, 3))
+    del xh
+    assert G.max_rel_err(dbeta.cpu().numpy(), db64.cpu().numpy(), G.rms(db64.cpu().numpy())) <= 1e-4
+    assert G.max_rel_err(dgamma.cpu().numpy(), dg64.cpu().numpy(), G.rms(dg64.cpu().numpy())) <= 1e-4
+    g64, b64 = gamma.cpu().numpy().astype(np.float64), beta.cpu().numpy().astype(np.float64)
+    for c in sorted({0, wl.C // 3, wl.C - 1}):
+        sl = slice(c, c + 1)
+        xs, ss, dys = (t[:, sl].cpu().numpy().astype(np.float64) for t in (x, sc, dy))
+        ys = y[:, sl].cpu().numpy().astype(np.float64)
+        y_ref, m_ref, i_ref = R.cgbn_relu_forward_ref(xs, g64[sl], b64[sl], wl.eps, wl.layout, residual=ss)
+        dx_ref, dg_ref, db_ref, dz_ref = R.cgbn_relu_backward_ref(dys, ys, xs, m_ref, i_ref, g64[sl], wl.layout)
+        got = dict(y=ys, mean=mean[sl].cpu().numpy().astype(np.float64), invstd=invstd[sl].cpu().numpy().astype(np.float64),
+                   dx=dx[:, sl].cpu().numpy().astype(np.float64), dgamma=dgamma[sl].cpu().numpy().astype(np.float64),
+                   dbeta=dbeta[sl].cpu().numpy().astype(np.float64), dz=dz[:, sl].cpu().numpy().astype(np.float64))
+        ref = dict(y=y_ref, mean=m_ref, invstd=i_ref, dx=dx_ref, dgamma=dg_ref, dbeta=db_ref, dz=dz_ref)
+        print(f"[ok] relu full size {name} channel {c}: {_check(got, ref, wl.dtype, f'{name} channel {c}')}", flush=True)

@@ -1,7 +1,7 @@
 """Build libcgbn.so for gfx950 in-tree with hipcc (cross-compiles without a GPU).
 
 The host code and the multi-sweep kernels are one translation unit; the NCHW
-single-launch kernels are instantiated in eight more (element type x direction
+single-launch kernels are instantiated in ten more (element type x direction
 x activation), compiled side by side, then everything is linked into one
 shared library."""
 
@@ -33,7 +33,7 @@ def _units():
     units = [(os.path.join(OBJ, "cgbn.o"), os.path.join(CSRC, "cgbn.hip"), [])]
     for tname, t in (("f32", "float"), ("bf16", "bf16_t")):
         for fwd in (1, 0):
-            for act in (0, 1):
+            for act in ((0, 1, 2) if fwd else (0, 1)):       # forward: plain, ReLU, shortcut + ReLU
                 obj = os.path.join(OBJ, f"fused_{tname}_{'fwd' if fwd else 'bwd'}_act{act}.o")
                 units.append((obj, os.path.join(CSRC, "cgbn_fused_inst.hip"),
                               [f"-DCGBN_INST_T={t}", f"-DCGBN_INST_FWD={fwd}", f"-DCGBN_INST_ACT={act}"]))

@@ -19,6 +19,8 @@ namespace cgbn {
 #define CGBN_DECL_F(LB_, LPPC_)                                                               \
     extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 0>(FusedArgs);     \
     extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 1>(FusedArgs);     \
+    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 2>(FusedArgs);     \
+    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 2>(FusedArgs);    \
     extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 0>(FusedArgs);    \
     extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 1>(FusedArgs);
 #define CGBN_DECL_B(LB_, LPPC_)                                                               \
@@ -693,7 +695,9 @@ cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, 
         bool taken = false;
         const int sync_words = kSyncHeader + 8 * p.C;
         const bool f32 = p.dtype == CGBN_F32;
-        cgbn_status st_ = relu ? (f32 ? launch_fused_t<float, true, 1>(p.ff, F, sync_words, st, &taken)
+        cgbn_status st_ = relu && shortcut ? (f32 ? launch_fused_t<float, true, 2>(p.ff, F, sync_words, st, &taken)
+                                                  : launch_fused_t<bf16_t, true, 2>(p.ff, F, sync_words, st, &taken))
+                        : relu ? (f32 ? launch_fused_t<float, true, 1>(p.ff, F, sync_words, st, &taken)
                                       : launch_fused_t<bf16_t, true, 1>(p.ff, F, sync_words, st, &taken))
                                : (f32 ? launch_fused_t<float, true, 0>(p.ff, F, sync_words, st, &taken)
                                       : launch_fused_t<bf16_t, true, 0>(p.ff, F, sync_words, st, &taken));

@@ -414,8 +414,8 @@ struct Slots {
 // ---------------------------------------------------------------------------
 // forward: Algorithm 1 steps 1-11 in one launch
 // ---------------------------------------------------------------------------
-// ACT != 0: y = max(0, step 11 + shortcut), the shortcut (A.aux, may be null) being read
-// a few slots at a time while the unit is written out.
+// ACT == 1: y = max(0, step 11).  ACT == 2: y = max(0, step 11 + shortcut), the shortcut
+// (A.aux) being read a few slots at a time while the unit is written out.
 template <typename T, int LB, int LPPC, int ACT>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 {
@@ -575,9 +575,9 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
         if (g.u == 0 && t == 0) A.invstd[c] = istd;
 
         // ---- step 11: normalise from registers, write y --------------------
-        if (ACT != 0 && A.aux != nullptr) {
+        if (ACT == 2) {
             // with a shortcut: its slots are fetched kBatch at a time, just before they are used
-            constexpr int kBatch = 8 / W;
+            constexpr int kBatch = 16 / W;
             const unsigned loff = SL::lane_offset(t);
             const float gsc = A.gamma[c] * istd, bsh = A.beta[c];
             const char* ru = static_cast<const char*>(A.aux) + g.base;

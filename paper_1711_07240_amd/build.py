@@ -28,8 +28,9 @@ FLAGS = [
 ]
 
 
-def _units():
+def _units(obj_dir):
     """(object file, source, extra flags) of every translation unit."""
+    OBJ = obj_dir
     units = [(os.path.join(OBJ, "cgbn.o"), os.path.join(CSRC, "cgbn.hip"), [])]
     for tname, t in (("f32", "float"), ("bf16", "bf16_t")):
         for fwd in (1, 0):
@@ -40,14 +41,16 @@ def _units():
     return units
 
 
-def build(verbose: bool = True, jobs: int | None = None) -> str:
-    os.makedirs(OBJ, exist_ok=True)
-    units = _units()
+def build(verbose: bool = True, jobs: int | None = None, extra_flags=(), lib: str = LIB, obj_dir: str = OBJ) -> str:
+    """Compile and link; `extra_flags` (e.g. a -D for an instrumented build), `lib` and
+    `obj_dir` let a second flavour of the library be built beside the product one."""
+    os.makedirs(obj_dir, exist_ok=True)
+    units = _units(obj_dir)
     jobs = jobs or max(1, min(len(units), int(os.environ.get("MAX_JOBS", os.cpu_count() or 1)), 16))
 
     def compile_one(u):
         obj, src, extra = u
-        cmd = [HIPCC] + FLAGS + extra + ["-c", src, "-o", obj]
+        cmd = [HIPCC] + FLAGS + list(extra_flags) + extra + ["-c", src, "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
@@ -55,11 +58,11 @@ def build(verbose: bool = True, jobs: int | None = None) -> str:
 
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(compile_one, units))
-    cmd = [HIPCC, "--offload-arch=gfx950", "-fno-gpu-rdc", "-shared", "-fPIC", "-o", LIB] + objs
+    cmd = [HIPCC, "--offload-arch=gfx950", "-fno-gpu-rdc", "-shared", "-fPIC", "-o", lib] + objs
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

@@ -76,6 +76,13 @@ SMALL = [
     ("nchw-f32-plane2900", dict(N=4, C=5, H=50, W=58, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane5000", dict(N=5, C=3, H=50, W=100, K=5, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane2600", dict(N=6, C=4, H=50, W=52, K=3, layout="NCHW", dtype="bf16")),
+    # small planes of 16m + 8 bytes (8-byte accesses; every other plane starts off a 16-byte boundary; the last
+    # plane ends exactly at the end of the tensor)
+    ("nchw-f32-plane6-8mod16", dict(N=6, C=3, H=2, W=3, K=3, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane258-8mod16", dict(N=8, C=5, H=6, W=43, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane7938-8mod16", dict(N=4, C=3, H=63, W=126, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane84-8mod16", dict(N=6, C=4, H=6, W=14, K=2, layout="NCHW", dtype="bf16")),
+    ("nchw-bf16-plane4100-8mod16", dict(N=4, C=3, H=50, W=82, K=4, layout="NCHW", dtype="bf16")),
     # large planes: tiles that spill past the registers into LDS slots, ragged last tile
     ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),

@@ -167,6 +167,23 @@ def measure_rotating(layer, torch, cgbn, steps, sets=4):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def measure_graph(layer, torch, steps):
+    """ms per step when forward + backward are captured once into a HIP graph and replayed:
+    what a launch-latency-bound shape costs without the per-launch host work."""
+    layer.step()
+    torch.cuda.synchronize()
+    graph, side = torch.cuda.CUDAGraph(), torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        layer.step()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def cpu_baseline(wl, synth, budget_s=12.0):
     """The float64 oracle (plain definition, forward + backward) on host cores,
     on channels of the same workload, sized to about `budget_s` seconds."""
@@ -221,7 +238,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg1")
-    ap.add_argument("--others", default="cfg2,cfg3,cfg4", help="secondary workloads timed with fewer steps ('' = none)")
+    ap.add_argument("--others", default="cfg0,cfg2,cfg3,cfg4", help="secondary workloads timed with fewer steps ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run the library's plain copy kernel over 1 GiB (for counter calibration under rocprofv3)")
@@ -312,7 +329,10 @@ def main():
         log(f"[bench] secondary workload {name}")
         l2 = Layer(w2, torch, cgbn, *device_inputs_fast(w2, torch, synth, dev))
         others.append(measure_workload(l2, torch, max(5, args.steps // 5), max(2, args.warmup // 2)))
-        if 4 * w2.S * w2.elem_bytes <= (2 << 30):
+        if w2.S * w2.elem_bytes <= (1 << 20):
+            # launch-latency bound (the tensors live in L2): also as a replayed HIP graph
+            others[-1]["ms_per_step_graph_replay"] = measure_graph(l2, torch, 200)
+        elif 4 * w2.S * w2.elem_bytes <= (2 << 30):
             # tensors near the size of the memory-side cache (256 MB): the figure above re-uses one
             # buffer set ("warm"), this one rotates over four ("cold")
             others[-1]["ms_per_step_rotating_4_buffer_sets"] = measure_rotating(l2, torch, cgbn, max(8, args.steps // 5))

@@ -24,7 +24,9 @@
  *     vectors are float[C]; shard partials are double[K*C], index k*C + c.
  *   - Shard k holds images [k*N/K, (k+1)*N/K); 1 <= K <= N and N % K == 0.
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL is
- *     the default stream).  No call synchronises or reads back.
+ *     the default stream).  No call synchronises, reads back or allocates, and scratch is
+ *     cleared by kernels, so a sequence of calls can be captured into a HIP graph and
+ *     replayed (with the same pointers).
  *   - Errors: the return code only.  Argument errors are found on the host
  *     before any launch and leave every output untouched.  CGBN_ERR_HIP wraps a
  *     failed launch.  NaN/Inf in the data are not errors; they propagate within

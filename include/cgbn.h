@@ -209,7 +209,8 @@ const char* cgbn_status_string(cgbn_status status);
  * change them only between calls and re-query cgbn_workspace_bytes afterwards).
  *   "chunk_bytes"      NCHW: bytes of one plane handled by one workgroup
  *   "wave_plane_bytes" NCHW: planes up to this size are handled by one wavefront
- *   "piece_bytes"      NHWC reductions: bytes of one pixel range handled by one workgroup
+ *   "piece_bytes"      NHWC reductions: bytes of one pixel range handled by one workgroup (0, the default:
+ *                      chosen per shape so that the grid fills the device's compute units evenly)
  *   "map_piece_bytes"  NHWC normalise / dx: the same for the elementwise sweeps
  *   "reverse"          0/1: alternate the sweep direction between consecutive sweeps
  *   "nt_store"         0/1: non-temporal stores for y and dx

@@ -57,8 +57,8 @@ struct SweepArgs {
     const float* beta;
     const float* dgamma;
     const float* dbeta;
-    float* part0;             // [C][rows]
-    float* part1;             // [C][rows]
+    float* part0;             // row partials: NCHW [C][rows], NHWC [rows][C] (a workgroup's channels side by side)
+    float* part1;
     long long S;              // elements in the tensor
     int N, C, HW, rows;
     // NCHW
@@ -588,7 +588,7 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
             s0 += sm[(0 * A.rpp + rr) * nout + o];
             if (Q == 2) s1 += sm[(1 * A.rpp + rr) * nout + o];
         }
-        size_t po = (size_t)ch * A.rows + row;
+        size_t po = (size_t)row * A.C + ch;          // consecutive threads, consecutive floats: whole lines per store
         A.part0[po] = s0;
         if (Q == 2) A.part1[po] = s1;
     }
@@ -666,8 +666,9 @@ __global__ __launch_bounds__(kThreads) void nhwc_map(SweepArgs A)
 // --------------------------------------------------------------------------
 
 struct CombineArgs {
-    const float* part0;   // [C][rows]
-    const float* part1;   // [C][rows] (CM_BWD only)
+    const float* part0;   // row r of channel c at c * cs + r * rs
+    const float* part1;   // the same (CM_BWD, CM_SHARDS2 only)
+    long long cs, rs;
     double* sh0;          // [K][C] shard sums out, may be null
     double* sh1;
     float* out0;          // mean | invstd | dbeta
@@ -708,14 +709,14 @@ __device__ __forceinline__ double shard_then_total(const float* pr, double* sh, 
         for (int u = 0; u < B; ++u) {
             int k = k0 + u * spp + gi;
             bool have = k < A.K && gl < A.rps;
-            float v = pr[have ? (size_t)k * A.rps + gl : 0];
+            float v = pr[have ? ((size_t)k * A.rps + gl) * A.rs : 0];
             acc[u] = have ? (double)v : 0.0;
         }
 #pragma unroll
         for (int u = 0; u < B; ++u) {
             int k = k0 + u * spp + gi;
             if (k < A.K)
-                for (int r = gl + G; r < A.rps; r += G) acc[u] += (double)pr[(size_t)k * A.rps + r];
+                for (int r = gl + G; r < A.rps; r += G) acc[u] += (double)pr[((size_t)k * A.rps + r) * A.rs];
             for (int off = G >> 1; off >= 1; off >>= 1) acc[u] += __shfl_xor(acc[u], off);
             if (k < A.K) {
                 if (sh && gl == 0) sh[(size_t)k * A.C + c] = acc[u] + shard_offset;
@@ -735,10 +736,10 @@ __global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
     if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     if (c >= A.C) return;
     const double pivot = pivot_of(A, c);      // zero unless the rows hold sums about a pivot
-    double t0 = shard_then_total(A.part0 + (size_t)c * A.rows, A.sh0, c, A, lane, pivot * A.shard_count);
+    double t0 = shard_then_total(A.part0 + (size_t)c * A.cs, A.sh0, c, A, lane, pivot * A.shard_count);
     double t1 = 0.0;
     if (MODE == CM_BWD || MODE == CM_SHARDS2)
-        t1 = shard_then_total(A.part1 + (size_t)c * A.rows, A.sh1, c, A, lane, 0.0);
+        t1 = shard_then_total(A.part1 + (size_t)c * A.cs, A.sh1, c, A, lane, 0.0);
     if (lane != 0) return;
     if (MODE == CM_MEAN) {
         double m = pivot + t0 / A.M;
@@ -780,8 +781,6 @@ __global__ __launch_bounds__(kThreads) void combine_shards(const double* s0, con
     }
 }
 
-// Plain copy of `nvec` 16-byte vectors, 8 per thread: reads and writes a known
-// number of bytes, for calibrating hardware traffic counters.
 // Exponential moving average of the pooled statistics (one thread per channel, float64).
 // The biased batch variance is recovered from invstd: var = 1/invstd^2 - eps.
 static __global__ __launch_bounds__(kThreads) void running_update(const float* mean, const float* mean_lo, const float* invstd,
@@ -799,6 +798,8 @@ static __global__ __launch_bounds__(kThreads) void running_update(const float* m
     running_var[c] = (float)(keep * (double)running_var[c] + momentum * (var * unbias));
 }
 
+// Plain copy of `nvec` 16-byte vectors, 8 per thread: reads and writes a known
+// number of bytes, for calibrating hardware traffic counters.
 static __global__ __launch_bounds__(kThreads) void calibration_copy(const u32x4* src, u32x4* dst, size_t nvec)
 {
     size_t i = (size_t)blockIdx.x * (kThreads * 8) + threadIdx.x;

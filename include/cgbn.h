@@ -215,7 +215,6 @@ const char* cgbn_status_string(cgbn_status status);
  *   "reverse"          0/1: alternate the sweep direction between consecutive sweeps
  *   "nt_store"         0/1: non-temporal stores for y and dx
  *   "fused"            0/1: register-resident single-launch forward/backward (NCHW)
- *   "fused_nhwc"       the same for NHWC: 0 never, 1 where measured to pay (default), 2 wherever the shape allows
  *   "fused_groups"     workgroups of that launch (0 = all that are resident at once)
  *   "spin_limit"       polls before a device-side wait gives up
  * cgbn_get_tuning returns -1 for an unknown key. */

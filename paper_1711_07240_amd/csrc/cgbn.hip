@@ -4,7 +4,6 @@
 #include "cgbn.h"
 #include "cgbn_kernels.h"
 #include "cgbn_fused.h"
-#include "cgbn_fused_nhwc.h"
 #include "cgbn_fused_list.h"
 
 #include <cmath>
@@ -51,7 +50,6 @@ struct Tuning {
     long long fused = 1;                 // register-resident single-launch path where the shape allows it
     long long spin_limit = 1LL << 24;    // polls of a bounded wait in the fused kernels before it gives up
     long long fused_groups = 0;          // workgroups of the fused grid (0 = as many as are resident at once)
-    long long fused_nhwc = 1;            // channels-last single-launch kernels: 0 never, 1 where they pay, 2 wherever possible
 };
 Tuning g_tune;
 long long g_last_forward_fused = 0, g_last_backward_fused = 0;   // which path the last call took
@@ -66,7 +64,6 @@ struct FusedPlan {
     int LB;               // bytes per load: 16 or 8
     int LPPC;             // 0: large planes; else register slots per plane (a power of two >= LPP)
     int tp, TL, LPP, IPU, U, rows, rps, G;
-    int nhwc, groups, ups, PU;   // channels-last: channel groups, units per shard, pixels per unit
     long long total_units;
 };
 
@@ -87,42 +84,16 @@ struct Plan {
     long long grid;       // workgroups of one sweep
     FusedPlan ff, fb;     // register-resident path, forward and backward
     // workspace layout (byte offsets)
-    size_t off_part0, off_part1, off_sh0, off_sh1, off_mlo, off_stat, off_sync, bytes;
+    size_t off_part0, off_part1, off_sh0, off_sh1, off_mlo, off_sync, bytes;
 };
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words, int nhwc_words,
-                     FusedPlan* f)
+void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words, FusedPlan* f)
 {
     std::memset(f, 0, sizeof(*f));
     if (K > kFusedMaxShards) return;
-    if (layout == CGBN_NHWC) {
-        // channel groups of 128 contiguous bytes per pixel, 4 channels per thread
-        if (((long long)C * eb) % kGroupBytes != 0) return;
-        const int LBn = 4 * eb, Wn = LBn / 4, Rn = nhwc_words / Wn + (LBn == 16 ? lds_words / Wn : 0);
-        const int PPP = kThreads / (kGroupBytes / LBn);
-        const long long PUmax = (long long)Rn * PPP, spix = (long long)(N / K) * HW;
-        long long ups = (spix + PUmax - 1) / PUmax;
-        long long PU = (spix + ups - 1) / ups;
-        PU = (PU + PPP - 1) / PPP * PPP;
-        ups = (spix + PU - 1) / PU;
-        if (ups * K > kFusedMaxRows || PU * C * eb > 0x7fffffffLL) return;
-        f->nhwc = 1;
-        f->LB = LBn;
-        f->groups = (int)((long long)C * eb / kGroupBytes);
-        f->ups = (int)ups;
-        f->PU = (int)PU;
-        f->U = (int)(ups * K);
-        f->rows = f->U;
-        f->rps = (int)ups;
-        f->total_units = (long long)f->groups * f->U;
-        int Gn = 1;
-        while (Gn < kWave && Gn < f->rps) Gn <<= 1;
-        f->G = Gn;
-        f->ok = 1;
-        return;
-    }
+    if (layout != CGBN_NCHW) return;                   // channels-last shapes take the multi-sweep kernels
     int LB = 0;
     for (int lb = 16; lb >= 8; lb >>= 1)
         if (HW % (lb / eb) == 0) { LB = lb; break; }
@@ -292,8 +263,8 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     int G = 1;
     while (G < kWave && G < p->rps) G <<= 1;
     p->G = G;
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kNhwcWordsFwd, &p->ff);
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kNhwcWordsBwd / 2, &p->fb);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, &p->ff);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, &p->fb);
     int max_rows = p->rows;
     if (p->ff.ok && p->ff.rows > max_rows) max_rows = p->ff.rows;
     if (p->fb.ok && p->fb.rows > max_rows) max_rows = p->fb.rows;
@@ -304,9 +275,8 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     p->off_sh0 = 2 * part;
     p->off_sh1 = 2 * part + sh;
     p->off_mlo = 2 * part + 2 * sh;
-    p->off_stat = p->off_mlo + align256((size_t)C * sizeof(float));
-    p->off_sync = p->off_stat + align256(3 * (size_t)C * sizeof(float));
-    p->bytes = p->off_sync + align256(((size_t)kSyncHeader + 8 * (size_t)C) * sizeof(unsigned));
+    p->off_sync = p->off_mlo + align256((size_t)C * sizeof(float));
+    p->bytes = p->off_sync + align256(((size_t)kSyncHeader + 4 * (size_t)C) * sizeof(unsigned));
     return CGBN_OK;
 }
 
@@ -451,13 +421,6 @@ cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A
     if (groups > f.total_units) groups = f.total_units;
     *taken = false;
     if (groups < 1 || f.U > groups) return CGBN_OK;      // a channel's units must all be resident: other path
-    if (f.nhwc) {
-        // Channels-last units wait through a two-stage hand-over; measured against the
-        // multi-sweep kernels they only win while enough channel groups are in flight to
-        // cover those waits (float: 5 or more, bfloat16: 16 or more).
-        if (g_tune.fused_nhwc == 0) return CGBN_OK;
-        if (g_tune.fused_nhwc == 1 && groups / f.U < (f.LB == 16 ? 5 : 16)) return CGBN_OK;
-    }
     // With few channels in flight, a grid that is not a whole number of channels leaves the
     // units of the straddling channel waiting a full round for their siblings: trim it.
     if (g_tune.fused_groups == 0 && groups / f.U < 8) groups = groups / f.U * f.U;
@@ -472,17 +435,11 @@ cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A
     return launched();
 }
 
-// ACT: the ReLU variants (NCHW only; channels-last shapes take the multi-sweep kernels then)
+// ACT: 0 plain, 1 ReLU, 2 shortcut + ReLU (forward only)
 template <typename T, bool FWD, int ACT>
 cgbn_status launch_fused_t(const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st, bool* taken)
 {
     *taken = false;
-    if (f.nhwc) {
-        constexpr int LBn = 4 * (int)sizeof(T);
-        if constexpr (ACT != 0) return CGBN_OK;
-        else if constexpr (FWD) return launch_fused_kernel(nhwc_fused_forward<T, LBn>, f, A, sync_words, st, taken);
-        else return launch_fused_kernel(nhwc_fused_backward<T, LBn>, f, A, sync_words, st, taken);
-    }
 #define CGBN_FUSED_CASE(LB_, LPPC_)                                                                          \
     if (f.LB == LB_ && f.LPPC == LPPC_) {                                                                    \
         if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT>, f, A, sync_words, st, taken); \
@@ -515,12 +472,6 @@ FusedArgs fused_args(const Plan& p, const FusedPlan& f, char* ws)
     A.nt = (int)g_tune.nt_store;
     A.spin_limit = (unsigned)g_tune.spin_limit;
     A.plane_stride = (unsigned)((long long)p.C * p.HW * p.eb);
-    A.stat0 = reinterpret_cast<float*>(ws + p.off_stat);
-    A.stat1 = A.stat0 + p.C;
-    A.stat2 = A.stat1 + p.C;
-    A.spix = (long long)p.ips * p.HW;
-    A.groups = f.groups; A.ups = f.ups; A.PU = f.PU;
-    A.row_bytes = (unsigned)((long long)p.C * p.eb);
 #ifdef CGBN_TRACE
     A.trace = g_trace;
 #endif
@@ -742,7 +693,7 @@ cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, 
         F.x = x; F.out = y; F.gamma = gamma; F.beta = beta; F.eps = (double)eps; F.aux = shortcut;
         F.mean = mean; F.mean_lo = mlo; F.mean_lo_user = mean_lo; F.invstd = invstd;
         bool taken = false;
-        const int sync_words = kSyncHeader + 8 * p.C;
+        const int sync_words = kSyncHeader + 4 * p.C;
         const bool f32 = p.dtype == CGBN_F32;
         cgbn_status st_ = relu && shortcut ? (f32 ? launch_fused_t<float, true, 2>(p.ff, F, sync_words, st, &taken)
                                                   : launch_fused_t<bf16_t, true, 2>(p.ff, F, sync_words, st, &taken))
@@ -795,7 +746,7 @@ cgbn_status backward_impl(const void* dy, const void* y, const void* x, const fl
         F.mean = const_cast<float*>(mean); F.mean_lo = const_cast<float*>(mean_lo);
         F.invstd = const_cast<float*>(invstd); F.dgamma = dgamma; F.dbeta = dbeta;
         bool taken = false;
-        const int sync_words = kSyncHeader + 8 * p.C;
+        const int sync_words = kSyncHeader + 4 * p.C;
         const bool f32 = p.dtype == CGBN_F32;
         cgbn_status st_ = relu ? (f32 ? launch_fused_t<float, false, 1>(p.fb, F, sync_words, st, &taken)
                                       : launch_fused_t<bf16_t, false, 1>(p.fb, F, sync_words, st, &taken))
@@ -894,7 +845,6 @@ static long long* tuning_slot(const char* key)
     if (!std::strcmp(key, "fused")) return &g_tune.fused;
     if (!std::strcmp(key, "spin_limit")) return &g_tune.spin_limit;
     if (!std::strcmp(key, "fused_groups")) return &g_tune.fused_groups;
-    if (!std::strcmp(key, "fused_nhwc")) return &g_tune.fused_nhwc;
     return nullptr;
 }
 
@@ -904,8 +854,6 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
     if (!slot) return CGBN_ERR_TUNING;
     if (slot == &g_tune.reverse || slot == &g_tune.nt_store || slot == &g_tune.fused) {
         if (value != 0 && value != 1) return CGBN_ERR_TUNING;
-    } else if (slot == &g_tune.fused_nhwc) {
-        if (value < 0 || value > 2) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.spin_limit) {
         if (value < 0 || value > 0xffffffffLL) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.fused_groups) {

@@ -78,7 +78,7 @@ struct FusedArgs {
     float* part1;
     double* sh0;          // [K][C]
     double* sh1;
-    unsigned* sync;       // [1] error word, [kSyncHeader ..) per-channel (or per-group) unit counters and flags
+    unsigned* sync;       // [1] error word, [kSyncHeader ..) per-channel unit counters and flags
     unsigned long long* trace;   // only used in builds with CGBN_TRACE
     long long total_units;
     double M, inv_M_f64, eps, shard_count;
@@ -91,13 +91,6 @@ struct FusedArgs {
     int nt;
     unsigned spin_limit;
     unsigned plane_stride; // small planes: bytes between the same channel's planes of consecutive images
-    // channels-last kernels (cgbn_fused_nhwc.h)
-    float* stat0;         // [C] statistics handed from the reducing workgroups to the others
-    float* stat1;
-    float* stat2;
-    long long spix;       // pixels per shard
-    int groups, ups, PU;  // channel groups, units per shard, pixels per unit
-    unsigned row_bytes;   // bytes of one pixel (all channels)
 };
 
 constexpr unsigned kRowSentinel = 0xffffffffu;

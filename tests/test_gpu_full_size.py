@@ -27,20 +27,8 @@ def _as_f64_dev(t, dtype):
     return t.to(torch.float64)
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg4b", "cfg4-single-launch", "cfg4b-single-launch"])
+@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg4b"])
 def test_full_size(name):
-    from paper_1711_07240_amd import cgbn as L
-    forced = name.endswith("-single-launch")      # the channels-last single-launch kernels, which the default skips at this size
-    name = name.split("-")[0]
-    L.cgbn_set_tuning("fused_nhwc", 2 if forced else 1)
-    try:
-        _full_size(name, forced)
-    finally:
-        L.cgbn_set_tuning("fused_nhwc", 1)
-
-
-def _full_size(name, forced):
-    from paper_1711_07240_amd import cgbn as L
     wl = synth.WORKLOADS[name]
     t0 = time.time()
     print(f"[case] {name}: generating {wl.S} elements x2 on the host", flush=True)
@@ -50,8 +38,6 @@ def _full_size(name, forced):
     p.forward()
     p.backward()
     torch.cuda.synchronize()
-    if forced:
-        assert L.cgbn_get_tuning("last_forward_fused") == 1 and L.cgbn_get_tuning("last_backward_fused") == 1
     print(f"[case] {name}: kernels done", flush=True)
 
     # ---- sampled channels, every element, against the oracle -------------

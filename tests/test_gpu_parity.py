@@ -18,12 +18,10 @@ pytestmark = pytest.mark.gpu
 def path(request):
     """Every test runs twice: with the register-resident single-launch kernels
     (where the shape allows them) and with the multi-sweep kernels only."""
-    old = L.cgbn_get_tuning("fused"), L.cgbn_get_tuning("fused_nhwc")
+    old = L.cgbn_get_tuning("fused")
     L.cgbn_set_tuning("fused", request.param)
-    L.cgbn_set_tuning("fused_nhwc", 2)      # channels-last: wherever the shape allows, not only where it pays
     yield request.param
-    L.cgbn_set_tuning("fused", old[0])
-    L.cgbn_set_tuning("fused_nhwc", old[1])
+    L.cgbn_set_tuning("fused", old)
 
 
 def oracle_all(x, dy, gamma, beta, eps, layout, dtype):
@@ -87,10 +85,10 @@ SMALL = [
     ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane90000", dict(N=2, C=2, H=300, W=300, K=2, layout="NCHW", dtype="bf16")),
-    # channels-last shapes that qualify for the single-launch kernels (128-byte channel groups)
+    # channels-last: several equal pieces per shard, long shards, few pixels
     ("nhwc-f32-c64", dict(N=4, C=64, H=19, W=23, K=2, layout="NHWC", dtype="f32")),
-    ("nhwc-f32-c32-two-units-per-shard", dict(N=3, C=32, H=37, W=41, K=3, layout="NHWC", dtype="f32")),
-    ("nhwc-f32-c96-few-units", dict(N=2, C=96, H=3, W=5, K=2, layout="NHWC", dtype="f32")),
+    ("nhwc-f32-c32-long-shards", dict(N=3, C=32, H=37, W=41, K=3, layout="NHWC", dtype="f32")),
+    ("nhwc-f32-c96-few-pixels", dict(N=2, C=96, H=3, W=5, K=2, layout="NHWC", dtype="f32")),
     ("nhwc-f32-c256-long-shard", dict(N=2, C=256, H=60, W=70, K=1, layout="NHWC", dtype="f32")),
     ("nhwc-bf16-c128", dict(N=4, C=128, H=33, W=35, K=2, layout="NHWC", dtype="bf16")),
     ("nhwc-bf16-c64-long-shard", dict(N=2, C=64, H=50, W=41, K=2, layout="NHWC", dtype="bf16")),

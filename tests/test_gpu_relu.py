@@ -18,12 +18,10 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(autouse=True, params=[1, 0], ids=["fused", "sweeps"])
 def path(request):
-    old = L.cgbn_get_tuning("fused"), L.cgbn_get_tuning("fused_nhwc")
+    old = L.cgbn_get_tuning("fused")
     L.cgbn_set_tuning("fused", request.param)
-    L.cgbn_set_tuning("fused_nhwc", 2)
     yield request.param
-    L.cgbn_set_tuning("fused", old[0])
-    L.cgbn_set_tuning("fused_nhwc", old[1])
+    L.cgbn_set_tuning("fused", old)
 
 
 BASE = synth.WORKLOADS["cfg1"]

@@ -329,6 +329,16 @@ def main():
         log(f"[bench] secondary workload {name}")
         l2 = Layer(w2, torch, cgbn, *device_inputs_fast(w2, torch, synth, dev))
         others.append(measure_workload(l2, torch, max(5, args.steps // 5), max(2, args.warmup // 2)))
+        if not others[-1]["single_launch"]["forward"]:
+            # the forward runs as separate sweeps: also with the one-sweep statistics variant (not Algorithm 1's
+            # two passes; 7 instead of 9 tensor sweeps per step, priced on its own byte count)
+            cgbn.cgbn_set_tuning("one_sweep_stats", 1)
+            v = measure_workload(l2, torch, max(5, args.steps // 5), 2)
+            cgbn.cgbn_set_tuning("one_sweep_stats", 0)
+            Sb2 = w2.S * w2.elem_bytes
+            others[-1]["one_sweep_stats_variant"] = dict(
+                ms_per_step=v["ms_per_step"], fwd_ms=v["fwd_ms"], algorithmic_bytes=7 * Sb2,
+                effective_GBps=7 * Sb2 / v["ms_per_step"] / 1e6, pct_of_peak=7 * Sb2 / v["ms_per_step"] / 1e6 / PEAK_GBPS * 100)
         if w2.S * w2.elem_bytes <= (1 << 20):
             # launch-latency bound (the tensors live in L2): also as a replayed HIP graph
             others[-1]["ms_per_step_graph_replay"] = measure_graph(l2, torch, 200)

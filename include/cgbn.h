@@ -215,6 +215,10 @@ const char* cgbn_status_string(cgbn_status status);
  *   "reverse"          0/1: alternate the sweep direction between consecutive sweeps
  *   "nt_store"         0/1: non-temporal stores for y and dx
  *   "fused"            0/1: register-resident single-launch forward/backward (NCHW)
+ *   "one_sweep_stats"  0/1 (default 0): where cgbn_forward runs as separate sweeps, take the statistics in ONE
+ *                      sweep -- per-shard (count, mean, M2) about a per-channel pivot, merged pairwise -- instead
+ *                      of Algorithm 1's two; same results up to rounding, 3 tensor sweeps instead of 4; loses
+ *                      accuracy only if a channel's first value lies many standard deviations from its mean
  *   "fused_groups"     workgroups of that launch (0 = all that are resident at once)
  *   "spin_limit"       polls before a device-side wait gives up
  * cgbn_get_tuning returns -1 for an unknown key. */

@@ -49,6 +49,7 @@ struct Tuning {
     long long nt_store = 1;              // non-temporal stores for y and dx
     long long fused = 1;                 // register-resident single-launch path where the shape allows it
     long long spin_limit = 1LL << 24;    // polls of a bounded wait in the fused kernels before it gives up
+    long long one_sweep_stats = 0;       // forward statistics in one sweep (a variant, not Algorithm 1's two passes)
     long long fused_groups = 0;          // workgroups of the fused grid (0 = as many as are resident at once)
 };
 Tuning g_tune;
@@ -343,6 +344,7 @@ cgbn_status launch_reduce(int op, const Plan& p, const SweepArgs& A, hipStream_t
     case OP_SUM:   f32 ? launch_reduce_t<float, OP_SUM>(p, A, st)   : launch_reduce_t<bf16_t, OP_SUM>(p, A, st); break;
     case OP_SQDEV: f32 ? launch_reduce_t<float, OP_SQDEV>(p, A, st) : launch_reduce_t<bf16_t, OP_SQDEV>(p, A, st); break;
     case OP_BWD:   f32 ? launch_reduce_t<float, OP_BWD>(p, A, st)   : launch_reduce_t<bf16_t, OP_BWD>(p, A, st); break;
+    case OP_MOMENTS: f32 ? launch_reduce_t<float, OP_MOMENTS>(p, A, st) : launch_reduce_t<bf16_t, OP_MOMENTS>(p, A, st); break;
     default:       f32 ? launch_reduce_t<float, OP_BWD_RELU>(p, A, st) : launch_reduce_t<bf16_t, OP_BWD_RELU>(p, A, st); break;
     }
     return launched();
@@ -366,14 +368,15 @@ cgbn_status launch_map(int el, const Plan& p, const SweepArgs& A, hipStream_t st
 // `pivot_x`: the activation tensor when the rows hold sums about the channel pivots
 // (the plain-sum sweep), else null.
 cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float* out1, float* out2,
-                           double* sh0, double* sh1, double eps, const void* pivot_x, hipStream_t st)
+                           double* sh0, double* sh1, double eps, const void* pivot_x, hipStream_t st,
+                           float* out3 = nullptr)
 {
     CombineArgs A;
     std::memset(&A, 0, sizeof(A));
     A.part0 = reinterpret_cast<const float*>(ws + p.off_part0);
     A.part1 = reinterpret_cast<const float*>(ws + p.off_part1);
     A.sh0 = sh0; A.sh1 = sh1;
-    A.out0 = out0; A.out1 = out1; A.out2 = out2;
+    A.out0 = out0; A.out1 = out1; A.out2 = out2; A.out3 = out3;
     A.M = p.M; A.eps = eps;
     A.shard_count = p.M / p.K;
     A.x = pivot_x;
@@ -388,6 +391,7 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
     case CM_INVSTD: hipLaunchKernelGGL((combine_rows<CM_INVSTD>), grid, block, 0, st, A); break;
     case CM_BWD:    hipLaunchKernelGGL((combine_rows<CM_BWD>), grid, block, 0, st, A); break;
     case CM_SHARDS2: hipLaunchKernelGGL((combine_rows<CM_SHARDS2>), grid, block, 0, st, A); break;
+    case CM_MOMENTS: hipLaunchKernelGGL((combine_rows<CM_MOMENTS>), grid, block, 0, st, A); break;
     default:        hipLaunchKernelGGL((combine_rows<CM_SHARDS1>), grid, block, 0, st, A); break;
     }
     return launched();
@@ -708,6 +712,16 @@ cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, 
 
     SweepArgs A = sweep_args(p);
     A.x = x; A.part0 = part0;
+    if (g_tune.one_sweep_stats) {
+        // Not Algorithm 1: one sweep leaves every shard's (count, mean, M2), merged pairwise into the
+        // pooled statistics; then step 11 as usual.  3 sweeps of the tensor instead of 4.
+        A.part1 = reinterpret_cast<float*>(ws + p.off_part1);
+        CGBN_TRY(launch_reduce(OP_MOMENTS, p, A, st));
+        CGBN_TRY(launch_combine(CM_MOMENTS, p, ws, mean, mlo, mean_lo, nullptr, nullptr, (double)eps, x, st, invstd));
+        A.mean = mean; A.mean_lo = mlo; A.invstd = invstd; A.gamma = gamma; A.beta = beta; A.out = y;
+        A.reverse = rev; A.dy = shortcut;
+        return launch_map(!relu ? EL_NORM : shortcut ? EL_NORM_ADD_RELU : EL_NORM_RELU, p, A, st);
+    }
     // steps 1-3 then 4-5
     CGBN_TRY(launch_reduce(OP_SUM, p, A, st));
     CGBN_TRY(launch_combine(CM_MEAN, p, ws, mean, mlo, mean_lo, sh0, nullptr, 0.0, x, st));
@@ -845,6 +859,7 @@ static long long* tuning_slot(const char* key)
     if (!std::strcmp(key, "fused")) return &g_tune.fused;
     if (!std::strcmp(key, "spin_limit")) return &g_tune.spin_limit;
     if (!std::strcmp(key, "fused_groups")) return &g_tune.fused_groups;
+    if (!std::strcmp(key, "one_sweep_stats")) return &g_tune.one_sweep_stats;
     return nullptr;
 }
 
@@ -852,7 +867,7 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
 {
     long long* slot = tuning_slot(key);
     if (!slot) return CGBN_ERR_TUNING;
-    if (slot == &g_tune.reverse || slot == &g_tune.nt_store || slot == &g_tune.fused) {
+    if (slot == &g_tune.reverse || slot == &g_tune.nt_store || slot == &g_tune.fused || slot == &g_tune.one_sweep_stats) {
         if (value != 0 && value != 1) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.spin_limit) {
         if (value < 0 || value > 0xffffffffLL) return CGBN_ERR_TUNING;

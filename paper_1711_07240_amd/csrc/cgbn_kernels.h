@@ -8,6 +8,8 @@
 //   reduce  OP_BWD    sum dy, sum dy*xhat         backward device sums
 //   map     EL_NORM   y  = gamma*(x-mean)*invstd + beta            step 11
 //   map     EL_DX     dx = gamma*invstd*(dy - dbeta/M - xhat*dgamma/M)
+//   reduce  OP_MOMENTS        sum (x - p), sum (x - p)^2 about the channel's pivot p: the one-sweep
+//                             statistics variant (not Algorithm 1's two passes)
 //   reduce  OP_BWD_RELU       the same sums of dz = dy where y > 0 (y: the stored output)
 //   map     EL_NORM_RELU      y  = max(0, step 11)
 //   map     EL_NORM_ADD_RELU  y  = max(0, step 11 + shortcut)
@@ -28,16 +30,17 @@ namespace cgbn {
 constexpr int kThreads = 256;   // 4 wavefronts per workgroup
 constexpr int kWave = 64;
 
-enum { OP_SUM = 0, OP_SQDEV = 1, OP_BWD = 2, OP_BWD_RELU = 3 };
+enum { OP_SUM = 0, OP_SQDEV = 1, OP_BWD = 2, OP_BWD_RELU = 3, OP_MOMENTS = 4 };
 enum { EL_NORM = 0, EL_DX = 1, EL_FROZEN = 2, EL_SCALE = 3, EL_NORM_RELU = 4, EL_NORM_ADD_RELU = 5, EL_DX_RELU = 6 };
 // which tensors a sweep reads besides x: `dy` (the second input: dy, or the shortcut) and
 // `aux` (the third: the stored output y, whose sign is the ReLU's mask)
 constexpr bool op_has_dy(int op) { return op == OP_BWD || op == OP_BWD_RELU; }
 constexpr bool op_has_y(int op) { return op == OP_BWD_RELU; }
+constexpr int op_sums(int op) { return (op_has_dy(op) || op == OP_MOMENTS) ? 2 : 1; }   // row partials per workgroup
 constexpr bool el_has_2(int el) { return el == EL_DX || el == EL_NORM_ADD_RELU || el == EL_DX_RELU; }
 constexpr bool el_has_3(int el) { return el == EL_DX_RELU; }
 constexpr bool el_is_norm(int el) { return el == EL_NORM || el == EL_NORM_RELU || el == EL_NORM_ADD_RELU; }
-enum { CM_MEAN = 0, CM_INVSTD = 1, CM_BWD = 2, CM_SHARDS1 = 3, CM_SHARDS2 = 4 };
+enum { CM_MEAN = 0, CM_INVSTD = 1, CM_BWD = 2, CM_SHARDS1 = 3, CM_SHARDS2 = 4, CM_MOMENTS = 5 };
 
 struct bf16_t { uint16_t bits; };
 
@@ -211,7 +214,7 @@ struct ChanConst {
 template <typename T, int OP> __device__ __forceinline__ ChanConst reduce_consts(const SweepArgs& A, int c)
 {
     ChanConst k = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    if (OP == OP_SUM) {
+    if (OP == OP_SUM || OP == OP_MOMENTS) {
         k.mu = Elem<T>::load1(static_cast<const T*>(A.x) + (long long)c * A.pivot_stride);
     } else {
         k.mu = A.mean[c];
@@ -254,6 +257,10 @@ template <int OP> __device__ __forceinline__ void accumulate(const ChanConst& k,
     if (op_has_y(OP)) dyv = yv > 0.f ? dyv : 0.f;
     if (OP == OP_SUM) {
         a0 += xv - k.mu;
+    } else if (OP == OP_MOMENTS) {
+        float d = xv - k.mu;
+        a0 += d;
+        a1 += d * d;
     } else if (OP == OP_SQDEV) {
         float d = (xv - k.mu) - k.mulo;
         a0 += d * d;
@@ -400,7 +407,7 @@ template <typename T, int OP>
 __global__ __launch_bounds__(kThreads) void nchw_reduce_block(SweepArgs A)
 {
     constexpr int VEC = Elem<T>::VEC;
-    constexpr int Q = op_has_dy(OP) ? 2 : 1;
+    constexpr int Q = op_sums(OP);
     __shared__ float sm[2 * 4];
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int j = (int)(b % A.sp);
@@ -435,7 +442,7 @@ template <typename T, int OP>
 __global__ __launch_bounds__(kThreads) void nchw_reduce_wave(SweepArgs A)
 {
     constexpr int VEC = Elem<T>::VEC;
-    constexpr int Q = op_has_dy(OP) ? 2 : 1;
+    constexpr int Q = op_sums(OP);
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
     long long plane = b * 4 + w;
@@ -512,7 +519,7 @@ __global__ __launch_bounds__(kThreads) void nchw_map_wave(SweepArgs A)
 template <typename T, int V, int OP>
 __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
 {
-    constexpr int Q = op_has_dy(OP) ? 2 : 1;
+    constexpr int Q = op_sums(OP);
     __shared__ float sm[Q * kThreads * V];
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int ct = (int)(b % A.ctiles);
@@ -674,6 +681,7 @@ struct CombineArgs {
     float* out0;          // mean | invstd | dbeta
     float* out1;          // mean_lo (workspace) | - | dgamma
     float* out2;          // mean_lo (caller, may be null)
+    float* out3;          // invstd (CM_MOMENTS)
     double M;
     double eps;
     double shard_count;   // values per shard and channel
@@ -728,6 +736,62 @@ __device__ __forceinline__ double shard_then_total(const float* pr, double* sh, 
     return tot;
 }
 
+// One-sweep statistics: a summary (count, mean, M2) of a set of values, M2 the sum of
+// squared deviations from the set's own mean, and the pairwise merge of two summaries.
+struct Moments {
+    double n, mean, m2;
+};
+__device__ __forceinline__ Moments merge_moments(const Moments& a, const Moments& b)
+{
+    Moments r;
+    r.n = a.n + b.n;
+    if (r.n == 0.0) return a;
+    const double d = b.mean - a.mean;
+    r.mean = a.mean + d * (b.n / r.n);
+    r.m2 = a.m2 + b.m2 + d * d * (a.n * b.n / r.n);
+    return r;
+}
+
+// Rows of sum(x - p) and sum((x - p)^2) -> one summary per shard (its mean taken about
+// the pivot p) -> all shards merged.  Shards are dealt to lane groups as in
+// shard_then_total; a lane merges its shards in order, then the 64 lanes merge in a
+// fixed tree (the lower lane always on the left).  Double precision throughout.
+__device__ __forceinline__ Moments merge_shard_moments(const float* p1, const float* p2, const CombineArgs& A, int lane)
+{
+    const int G = A.G;
+    const int gl = lane & (G - 1), gi = lane / G, spp = kWave / G;
+    Moments mine = {0.0, 0.0, 0.0};
+    for (int k0 = 0; k0 < A.K; k0 += spp) {
+        const int k = k0 + gi;
+        double s1 = 0.0, s2 = 0.0;
+        if (k < A.K)
+            for (int r = gl; r < A.rps; r += G) {
+                s1 += (double)p1[((size_t)k * A.rps + r) * A.rs];
+                s2 += (double)p2[((size_t)k * A.rps + r) * A.rs];
+            }
+        for (int off = G >> 1; off >= 1; off >>= 1) {
+            s1 += __shfl_xor(s1, off);
+            s2 += __shfl_xor(s2, off);
+        }
+        if (k < A.K && gl == 0) {
+            Moments sk;
+            sk.n = A.shard_count;
+            sk.mean = s1 / sk.n;                     // about the pivot
+            sk.m2 = s2 - s1 * sk.mean;               // sum (x-p)^2 - n * mean^2
+            if (sk.m2 < 0.0) sk.m2 = 0.0;
+            mine = merge_moments(mine, sk);
+        }
+    }
+    for (int off = 1; off < kWave; off <<= 1) {
+        Moments other;
+        other.n = __shfl_xor(mine.n, off);
+        other.mean = __shfl_xor(mine.mean, off);
+        other.m2 = __shfl_xor(mine.m2, off);
+        mine = (lane & off) ? merge_moments(other, mine) : merge_moments(mine, other);
+    }
+    return mine;
+}
+
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
 {
@@ -736,6 +800,18 @@ __global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
     if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     if (c >= A.C) return;
     const double pivot = pivot_of(A, c);      // zero unless the rows hold sums about a pivot
+    if (MODE == CM_MOMENTS) {
+        Moments m = merge_shard_moments(A.part0 + (size_t)c * A.cs, A.part1 + (size_t)c * A.cs, A, lane);
+        if (lane != 0) return;
+        double mean = pivot + m.mean;
+        float hi = (float)mean;
+        float lo = (float)(mean - (double)hi);
+        A.out0[c] = hi;
+        A.out1[c] = lo;
+        if (A.out2) A.out2[c] = lo;
+        A.out3[c] = (float)(1.0 / sqrt(m.m2 / A.M + A.eps));
+        return;
+    }
     double t0 = shard_then_total(A.part0 + (size_t)c * A.cs, A.sh0, c, A, lane, pivot * A.shard_count);
     double t1 = 0.0;
     if (MODE == CM_BWD || MODE == CM_SHARDS2)

@@ -206,14 +206,17 @@ def cpu_baseline(wl, synth, budget_s=12.0):
     t_one = time.perf_counter() - t
     rounds = max(1, min(wl.C // workers, int(budget_s / max(t_one, 1e-3))))
     chans = list(range(workers * rounds))
+    # when the whole layer is too little work, go over its channels more than once (>= ~10 s of CPU work)
+    reps = max(1, min(8, int(round(10.0 / max(t_one * len(chans), 1e-3)))))
     with ThreadPoolExecutor(max_workers=workers) as ex:
         inputs = list(ex.map(draw, chans))              # untimed
         t = time.perf_counter()
-        list(ex.map(run, inputs))
-        wall = time.perf_counter() - t
+        for _ in range(reps):
+            list(ex.map(run, inputs))
+        wall = (time.perf_counter() - t) / reps
     return dict(value=per * len(chans) / wall / 1e9, unit="GB/s", cores=workers, kind="oracle",
                 sample=f"{len(chans)} of {wl.C} channels of {wl.name}, forward+backward, float64 numpy, "
-                       f"{workers} threads with one channel each, {wall:.2f} s wall",
+                       f"{workers} threads with one channel each, {reps} pass(es), {wall:.2f} s wall per pass",
                 ms_per_layer_extrapolated=wall / len(chans) * wl.C * 1e3)
 
 

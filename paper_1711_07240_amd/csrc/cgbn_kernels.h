@@ -8,14 +8,14 @@
 //   reduce  OP_BWD    sum dy, sum dy*xhat         backward device sums
 //   map     EL_NORM   y  = gamma*(x-mean)*invstd + beta            step 11
 //   map     EL_DX     dx = gamma*invstd*(dy - dbeta/M - xhat*dgamma/M)
-//   reduce  OP_MOMENTS        sum (x - p), sum (x - p)^2 about the channel's pivot p: the one-sweep
-//                             statistics variant (not Algorithm 1's two passes)
-//   reduce  OP_BWD_RELU       the same sums of dz = dy where y > 0 (y: the stored output)
+//   reduce  OP_BWD_RELU       sum dz, sum dz*xhat with dz = dy where y > 0 (y: the stored output), else 0
 //   map     EL_NORM_RELU      y  = max(0, step 11)
 //   map     EL_NORM_ADD_RELU  y  = max(0, step 11 + shortcut)
 //   map     EL_DX_RELU        dx from dz; optionally writes dz, the shortcut's gradient
-//   map     EL_FROZEN y  = gamma*(x-m)/sqrt(s2+eps) + beta   fixed statistics m, s2 (sections 3.1, 3.3)
-//   map     EL_SCALE  dx = dy*gamma/sqrt(s2+eps)             backward of the fixed-statistics layer
+//   map     EL_FROZEN         y  = gamma*(x-m)/sqrt(s2+eps) + beta with fixed statistics m, s2 (sections 3.1, 3.3)
+//   map     EL_SCALE          dx = dy*gamma/sqrt(s2+eps), the backward of the fixed-statistics layer
+//   reduce  OP_MOMENTS        sum (x - p), sum (x - p)^2 about the channel's pivot p: the one-sweep
+//                             statistics variant (not Algorithm 1's two passes)
 // A reduce sweep leaves one float per (channel, row) in `part`, where the rows
 // of a channel are ordered shard by shard; combine_rows then adds the rows of a
 // shard (the device sum of Algorithm 1) and the shards (its reduce step) in

@@ -63,7 +63,7 @@ unsigned long long* g_trace = nullptr;
 struct FusedPlan {
     int ok;               // shape can take the path at all (grid size is checked at launch)
     int LB;               // bytes per load: 16 or 8
-    int LPPC;             // 0: large planes; else register slots per plane (a power of two >= LPP)
+    int LPPC;             // 0: large planes; else register slots per plane (an instantiated count >= LPP)
     int tp, TL, LPP, IPU, U, rows, rps, G;
     long long total_units;
 };

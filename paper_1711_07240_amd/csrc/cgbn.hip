@@ -170,18 +170,18 @@ long long reduce_pieces(long long spix, int K, int ctiles, int rpp, long long ti
 {
     const long long quantum = 4LL * rpp;                 // four pixels per thread and pass
     const int cus = compute_units();
-    long long best_pps = 1;
+    const long long max_pixels = (4LL << 20) / tile_row_bytes > quantum ? (4LL << 20) / tile_row_bytes : quantum;
+    const long long first = (spix + max_pixels - 1) / max_pixels;      // fewest pieces of at most 4 MiB
+    long long best_pps = first;
     double best = -1.0;
-    for (long long pps = 1; pps <= 256; ++pps) {
+    for (long long pps = first; pps <= first + 2LL * cus; ++pps) {
         long long PL = (spix + pps - 1) / pps;
         PL = (PL + quantum - 1) / quantum * quantum;
-        const long long bytes = PL * tile_row_bytes;
-        if (bytes > (4LL << 20) && PL > quantum) continue;           // too long: more pieces
-        if (bytes < (128LL << 10) && pps > 1) break;                  // too short from here on
+        if (PL * tile_row_bytes < (128LL << 10) && pps > first) break;   // too short from here on
         const long long grid = (spix + PL - 1) / PL * K * ctiles;
         const long long rounds = (grid + cus - 1) / cus;
         const double fill = (double)grid / (double)(rounds * cus);
-        if (fill > best + 0.02) { best = fill; best_pps = pps; }     // ties go to fewer pieces
+        if (fill > best + 0.02) { best = fill; best_pps = pps; }         // ties go to fewer pieces
         if (fill > 0.98) break;
     }
     long long PL = (spix + best_pps - 1) / best_pps;

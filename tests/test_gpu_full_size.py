@@ -97,3 +97,46 @@ def test_full_size(name):
         assert torch.all(dx64.sum(dim=dims_).abs() <= budget), name
         del dx64, dy64
     print(f"[ok] {name}: all {wl.C} channels pass the property and library checks", flush=True)
+
+
+@pytest.mark.parametrize("layout", ["NCHW", "NHWC"])
+def test_more_than_2_to_31_elements(layout):
+    """A tensor of 2.36e9 elements (9.4 GB per tensor): 64-bit indexing end to end.  Drawn on the device; the
+    first, a middle and the last channel element by element against the oracle, the last one holding the
+    elements with the highest addresses."""
+    from oracle import cgbn_oracle as O
+    from paper_1711_07240_amd import cgbn as L
+    N, C, H, W, K, eps = 32, 128, 512, 1125, 8, 1e-5
+    S = N * C * H * W
+    assert S > 2 ** 31
+    print(f"[case] {S} elements, {layout}", flush=True)
+    shape = (N, C, H, W) if layout == "NCHW" else (N, H, W, C)
+    bs = (1, -1, 1, 1) if layout == "NCHW" else (1, 1, 1, -1)
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(77)
+    mu = torch.linspace(-2, 2, C, device=dev).view(bs)
+    x = torch.empty(shape, device=dev).normal_(generator=gen).mul_(1.5).add_(mu)
+    dy = torch.empty(shape, device=dev).normal_(generator=gen)
+    y, dx = torch.empty_like(x), torch.empty_like(x)
+    gamma = torch.linspace(0.5, 1.5, C, device=dev)
+    beta = torch.linspace(-0.1, 0.1, C, device=dev)
+    f = dict(dtype=torch.float32, device=dev)
+    mean, invstd, mean_lo, dgamma, dbeta = (torch.empty(C, **f) for _ in range(5))
+    ws = torch.empty(L.cgbn_workspace_bytes(N, C, H, W, layout, "f32", K), dtype=torch.uint8, device=dev)
+    L.cgbn_forward(x, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, "f32", mean_lo, ws)
+    L.cgbn_backward(dy, x, mean, invstd, gamma, dx, dgamma, dbeta, N, C, H, W, layout, K, "f32", mean_lo, ws)
+    torch.cuda.synchronize()
+    err = ws[L.cgbn_workspace_error_offset(N, C, H, W, layout, "f32", K):][:4].view(torch.int32)
+    assert int(err.item()) == 0
+    for c in (0, C // 2 + 1, C - 1):
+        sl = slice(c, c + 1)
+        pick = (lambda t: t[:, sl]) if layout == "NCHW" else (lambda t: t[..., sl])
+        xs, dys = (pick(t).cpu().numpy().astype(np.float64) for t in (x, dy))
+        g1, b1 = gamma[sl].cpu().numpy().astype(np.float64), beta[sl].cpu().numpy().astype(np.float64)
+        ref = O.cgbn_forward_backward_ref(xs, dys, g1, b1, eps, layout)
+        got = dict(y=pick(y).cpu().numpy().astype(np.float64), dx=pick(dx).cpu().numpy().astype(np.float64),
+                   mean=mean[sl].cpu().numpy().astype(np.float64), mean_lo=mean_lo[sl].cpu().numpy().astype(np.float64),
+                   invstd=invstd[sl].cpu().numpy().astype(np.float64), dgamma=dgamma[sl].cpu().numpy().astype(np.float64),
+                   dbeta=dbeta[sl].cpu().numpy().astype(np.float64))
+        print(f"[ok] channel {c}: {check_against_oracle(got, ref, 'f32', f'{layout} channel {c}')}", flush=True)

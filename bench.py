@@ -207,7 +207,7 @@ def cpu_baseline(wl, synth, budget_s=12.0):
     rounds = max(1, min(wl.C // workers, int(budget_s / max(t_one, 1e-3))))
     chans = list(range(workers * rounds))
     # when the whole layer is too little work, go over its channels more than once (>= ~10 s of CPU work)
-    reps = max(1, min(8, int(round(10.0 / max(t_one * len(chans), 1e-3)))))
+    reps = max(1, min(8, int(-(-10.0 // max(t_one * len(chans), 1e-3)))))
     with ThreadPoolExecutor(max_workers=workers) as ex:
         inputs = list(ex.map(draw, chans))              # untimed
         t = time.perf_counter()

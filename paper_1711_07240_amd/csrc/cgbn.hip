@@ -429,7 +429,7 @@ cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A
     // units of the straddling channel waiting a full round for their siblings: trim it.
     if (g_tune.fused_groups == 0 && groups / f.U < 8) groups = groups / f.U * f.U;
     *taken = true;
-    {
+    if (f.U > 1) {      // a channel's only unit hands nothing over: no rows or counters to prepare
         long long want = (A.row_words + kThreads - 1) / kThreads;
         unsigned init_groups = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
         hipLaunchKernelGGL(fused_init, dim3(init_groups), dim3(kThreads), 0, st, A.sync, sync_words,

@@ -426,6 +426,10 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
     char* yb = static_cast<char*>(A.out);
     uint32_t d[kFusedWords];
     __shared__ uint32_t ext[RL > 0 ? RL * W * kThreads : 1];
+    // A unit that is its channel's only one keeps its rows in LDS: nothing is published, counted or waited
+    // for, and the launch needs no initialised workspace (the error word is cleared here instead).
+    const bool solo = A.U == 1;
+    if (solo && blockIdx.x == 0 && t == 0) A.sync[1] = 0u;
 
     for (long long unit = blockIdx.x; unit < A.total_units; unit += gridDim.x) {
         UnitGeom g;
@@ -478,7 +482,10 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                     int n = SL::image(g, s, w);
                     if (n < g.n1) {
                         float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                        if (lane == 0) publish_row(&A.part0[(size_t)c * A.rows + n], tot);
+                        if (lane == 0) {
+                            if (solo) lds.rows[0][n] = tot;
+                            else publish_row(&A.part0[(size_t)c * A.rows + n], tot);
+                        }
                     }
                     acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
                 }
@@ -487,10 +494,15 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                 float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
                 if (lane == 0) s_red[w] = tot;
                 __syncthreads();
-                if (t == 0) publish_row(&A.part0[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
+                if (t == 0) {
+                    const float tot4 = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+                    if (solo) lds.rows[0][g.u] = tot4;
+                    else publish_row(&A.part0[(size_t)c * A.rows + g.u], tot4);
+                }
             }
         }
-        count_in(A.sync + kSyncHeader + c, A.sync + kSyncHeader + 2 * A.C + c, A.U);
+        if (solo) __syncthreads();
+        else count_in(A.sync + kSyncHeader + c, A.sync + kSyncHeader + 2 * A.C + c, A.U);
         CGBN_STAMP(1);
         // ---- steps 4-5: when all rows are in, reduce them to the pooled mean
         bool ok1 = false;
@@ -498,7 +510,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
         // prove to run stops it from hoisting that block's index arithmetic out of the
         // unit loop, which would push the register-resident unit into scratch memory.
         if (A.rows > 0) {
-            ok1 = gather_rows<1>(A, A.part0 + (size_t)c * A.rows, nullptr, 1, A.sync + kSyncHeader + 2 * A.C + c, lds);
+            ok1 = solo || gather_rows<1>(A, A.part0 + (size_t)c * A.rows, nullptr, 1, A.sync + kSyncHeader + 2 * A.C + c, lds);
             CGBN_STAMP(2);
             reduce_rows<1, ST_MEAN>(A, c, lds, (double)pivot, g.u == 0);
         }
@@ -541,7 +553,10 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                     int n = SL::image(g, s, w);
                     if (n < g.n1) {
                         float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                        if (lane == 0) publish_row(&A.part1[(size_t)c * A.rows + n], tot);
+                        if (lane == 0) {
+                            if (solo) lds.rows[0][n] = tot;
+                            else publish_row(&A.part1[(size_t)c * A.rows + n], tot);
+                        }
                     }
                     acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
                 }
@@ -550,15 +565,20 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                 float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
                 if (lane == 0) s_red[w] = tot;
                 __syncthreads();
-                if (t == 0) publish_row(&A.part1[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
+                if (t == 0) {
+                    const float tot4 = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+                    if (solo) lds.rows[0][g.u] = tot4;
+                    else publish_row(&A.part1[(size_t)c * A.rows + g.u], tot4);
+                }
             }
         }
-        count_in(A.sync + kSyncHeader + A.C + c, A.sync + kSyncHeader + 3 * A.C + c, A.U);
+        if (solo) __syncthreads();
+        else count_in(A.sync + kSyncHeader + A.C + c, A.sync + kSyncHeader + 3 * A.C + c, A.U);
         CGBN_STAMP(4);
         // ---- steps 9-10: reduce to the variance and 1/sqrt(var + eps)
         bool ok2 = false;
         if (A.rows > 0) {
-            ok2 = gather_rows<1>(A, A.part1 + (size_t)c * A.rows, nullptr, 1, A.sync + kSyncHeader + 3 * A.C + c, lds);
+            ok2 = solo || gather_rows<1>(A, A.part1 + (size_t)c * A.rows, nullptr, 1, A.sync + kSyncHeader + 3 * A.C + c, lds);
             CGBN_STAMP(5);
             reduce_rows<1, ST_INVSTD>(A, c, lds, 0.0, g.u == 0, 1);
         }
@@ -665,6 +685,8 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
     char* ob = static_cast<char*>(A.out);
     uint32_t xd[kFusedWords / 2], gd[kFusedWords / 2];
     __shared__ uint32_t ext[RL > 0 ? 2 * RL * W * kThreads : 1];    // dy slots, then x slots
+    const bool solo = A.U == 1;     // the channel's only unit: rows stay in LDS (see the forward kernel)
+    if (solo && blockIdx.x == 0 && t == 0) A.sync[1] = 0u;
 
     for (long long unit = blockIdx.x; unit < A.total_units; unit += gridDim.x) {
         UnitGeom g;
@@ -776,8 +798,13 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                     if (n < g.n1) {
                         float ta = wave_sum(a[0] + a[1]), tb = wave_sum(b[0] + b[1]);
                         if (lane == 0) {
-                            publish_row(&A.part0[(size_t)c * A.rows + n], ta);
-                            publish_row(&A.part1[(size_t)c * A.rows + n], tb);
+                            if (solo) {
+                                lds.rows[0][n] = ta;
+                                lds.rows[1][n] = tb;
+                            } else {
+                                publish_row(&A.part0[(size_t)c * A.rows + n], ta);
+                                publish_row(&A.part1[(size_t)c * A.rows + n], tb);
+                            }
                         }
                     }
                     a[0] = a[1] = b[0] = b[1] = 0.f;
@@ -788,16 +815,24 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                 if (lane == 0) { s_red[w] = ta; s_red[4 + w] = tb; }
                 __syncthreads();
                 if (t == 0) {
-                    publish_row(&A.part0[(size_t)c * A.rows + g.u], (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]));
-                    publish_row(&A.part1[(size_t)c * A.rows + g.u], (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]));
+                    const float ta4 = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
+                    const float tb4 = (s_red[4] + s_red[5]) + (s_red[6] + s_red[7]);
+                    if (solo) {
+                        lds.rows[0][g.u] = ta4;
+                        lds.rows[1][g.u] = tb4;
+                    } else {
+                        publish_row(&A.part0[(size_t)c * A.rows + g.u], ta4);
+                        publish_row(&A.part1[(size_t)c * A.rows + g.u], tb4);
+                    }
                 }
             }
         }
-        count_in(A.sync + kSyncHeader + c, A.sync + kSyncHeader + 2 * A.C + c, A.U);
+        if (solo) __syncthreads();
+        else count_in(A.sync + kSyncHeader + c, A.sync + kSyncHeader + 2 * A.C + c, A.U);
         CGBN_STAMP(1);
         bool ok1 = false;
         if (A.rows > 0) {
-            ok1 = gather_rows<2>(A, A.part0 + (size_t)c * A.rows, A.part1 + (size_t)c * A.rows, 1,
+            ok1 = solo || gather_rows<2>(A, A.part0 + (size_t)c * A.rows, A.part1 + (size_t)c * A.rows, 1,
                                   A.sync + kSyncHeader + 2 * A.C + c, lds);
             CGBN_STAMP(2);
             reduce_rows<2, ST_SUMS>(A, c, lds, 0.0, g.u == 0);

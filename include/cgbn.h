@@ -38,6 +38,13 @@
  *     mean to about double precision.  The forward uses it internally in any
  *     case; exporting it lets the backward see the same mean when |mean| is
  *     orders of magnitude above the channel's spread.
+ *   - Concurrency: calls on ONE stream, or on several streams as long as they do not run at
+ *     the same time, need nothing special.  cgbn_forward / cgbn_backward calls that may
+ *     overlap in time on one device (different streams, each with its own workspace) must
+ *     set the "cooperative" knob first: their single-launch kernels wait for sibling
+ *     workgroups, and two such grids dispatched together could each end up half resident and
+ *     starve the other until the bounded waits give up (error word set, NaN statistics).
+ *     A workspace must never be shared by calls that can overlap.
  *   - Results are bitwise reproducible run to run (fixed summation order, no
  *     floating-point atomics) and depend on K only through rounding.
  */
@@ -219,6 +226,9 @@ const char* cgbn_status_string(cgbn_status status);
  *                      sweep -- per-shard (count, mean, M2) about a per-channel pivot, merged pairwise -- instead
  *                      of Algorithm 1's two; same results up to rounding, 3 tensor sweeps instead of 4; loses
  *                      accuracy only if a channel's first value lies many standard deviations from its mean
+ *   "cooperative"      0/1 (default 0): launch the single-launch kernels cooperatively, so that the runtime
+ *                      guarantees the whole grid is resident; needed only if such calls can overlap on
+ *                      different streams; costs about 15 us per launch
  *   "fused_groups"     workgroups of that launch (0 = all that are resident at once)
  *   "spin_limit"       polls before a device-side wait gives up
  * cgbn_get_tuning returns -1 for an unknown key. */

@@ -49,6 +49,7 @@ struct Tuning {
     long long nt_store = 1;              // non-temporal stores for y and dx
     long long fused = 1;                 // register-resident single-launch path where the shape allows it
     long long spin_limit = 1LL << 24;    // polls of a bounded wait in the fused kernels before it gives up
+    long long cooperative = 0;           // launch the single-launch kernels cooperatively (co-residency guaranteed by the runtime)
     long long one_sweep_stats = 0;       // forward statistics in one sweep (a variant, not Algorithm 1's two passes)
     long long fused_groups = 0;          // workgroups of the fused grid (0 = as many as are resident at once)
 };
@@ -434,6 +435,19 @@ cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A
         unsigned init_groups = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
         hipLaunchKernelGGL(fused_init, dim3(init_groups), dim3(kThreads), 0, st, A.sync, sync_words,
                            reinterpret_cast<unsigned*>(A.part0), A.row_words);
+    }
+    if (f.U > 1 && g_tune.cooperative) {
+        // Units wait for sibling units, so the whole grid must be resident at once.  Alone on the device it
+        // is (the grid is sized for that); a cooperative launch makes the runtime guarantee it also when
+        // another such launch is in flight on a different stream, where two half-resident grids could
+        // otherwise starve each other until their bounded waits give up.
+        void* args[] = {static_cast<void*>(&A)};
+        if (hipLaunchCooperativeKernel(reinterpret_cast<const void*>(kernel), dim3((unsigned)groups), dim3(kThreads),
+                                       args, 0, st) != hipSuccess) {
+            (void)hipGetLastError();
+            return CGBN_ERR_HIP;
+        }
+        return CGBN_OK;
     }
     hipLaunchKernelGGL(kernel, dim3((unsigned)groups), dim3(kThreads), 0, st, A);
     return launched();
@@ -860,6 +874,7 @@ static long long* tuning_slot(const char* key)
     if (!std::strcmp(key, "spin_limit")) return &g_tune.spin_limit;
     if (!std::strcmp(key, "fused_groups")) return &g_tune.fused_groups;
     if (!std::strcmp(key, "one_sweep_stats")) return &g_tune.one_sweep_stats;
+    if (!std::strcmp(key, "cooperative")) return &g_tune.cooperative;
     return nullptr;
 }
 
@@ -867,7 +882,8 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
 {
     long long* slot = tuning_slot(key);
     if (!slot) return CGBN_ERR_TUNING;
-    if (slot == &g_tune.reverse || slot == &g_tune.nt_store || slot == &g_tune.fused || slot == &g_tune.one_sweep_stats) {
+    if (slot == &g_tune.reverse || slot == &g_tune.nt_store || slot == &g_tune.fused || slot == &g_tune.one_sweep_stats ||
+        slot == &g_tune.cooperative) {
         if (value != 0 && value != 1) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.spin_limit) {
         if (value < 0 || value > 0xffffffffLL) return CGBN_ERR_TUNING;

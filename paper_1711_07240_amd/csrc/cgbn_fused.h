@@ -169,7 +169,7 @@ template <> struct Packed<bf16_t> {
         f[0] = __uint_as_float(w << 16);
         f[1] = __uint_as_float(w & 0xffff0000u);
     }
-    static __device__ __forceinline__ uint32_t pack(const float (&f)[2]) { return f32_to_bf16(f[0]) | (f32_to_bf16(f[1]) << 16); }
+    static __device__ __forceinline__ uint32_t pack(const float (&f)[2]) { return f32x2_to_bf16x2(f[0], f[1]); }
 };
 
 // ReLU mask on packed words: keeps the elements of `g` whose partner in `y` is > 0

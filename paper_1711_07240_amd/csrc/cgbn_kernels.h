@@ -82,14 +82,16 @@ struct SweepArgs {
 
 __device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
-// round to nearest even; NaN stays a quiet NaN
-__device__ __forceinline__ uint32_t f32_to_bf16(float f)
+// Two floats to two bfloat16 in one register (the first in the low half): gfx950's own
+// conversion instruction, round to nearest even, NaN stays a quiet NaN.
+typedef __bf16 bf16x2_hw __attribute__((ext_vector_type(2)));
+typedef float f32x2_hw __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
+    f32x2_hw v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_hw));
 }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) { return f32x2_to_bf16x2(f, 0.f) & 0xffffu; }
 
 template <typename T> struct Elem;
 
@@ -125,10 +127,10 @@ template <> struct Elem<bf16_t> {
     static __device__ __forceinline__ void storev(bf16_t* p, const float (&f)[8], int nt)
     {
         u32x4 v;
-        v.x = f32_to_bf16(f[0]) | (f32_to_bf16(f[1]) << 16);
-        v.y = f32_to_bf16(f[2]) | (f32_to_bf16(f[3]) << 16);
-        v.z = f32_to_bf16(f[4]) | (f32_to_bf16(f[5]) << 16);
-        v.w = f32_to_bf16(f[6]) | (f32_to_bf16(f[7]) << 16);
+        v.x = f32x2_to_bf16x2(f[0], f[1]);
+        v.y = f32x2_to_bf16x2(f[2], f[3]);
+        v.z = f32x2_to_bf16x2(f[4], f[5]);
+        v.w = f32x2_to_bf16x2(f[6], f[7]);
         if (nt) __builtin_nontemporal_store(v, reinterpret_cast<u32x4*>(p));
         else *reinterpret_cast<u32x4*>(p) = v;
     }

@@ -97,18 +97,19 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
     if (K > kFusedMaxShards) return;
     if (layout != CGBN_NCHW) return;                   // channels-last shapes take the multi-sweep kernels
     int LB = 0;
-    for (int lb = 16; lb >= 8; lb >>= 1)
+    for (int lb = 16; lb >= 4; lb >>= 1)
         if (HW % (lb / eb) == 0) { LB = lb; break; }
-    if (!LB) return;                                   // planes that are not a whole number of 8-byte loads
+    if (!LB) return;                                   // bfloat16 planes with an odd element count
     const int W = LB / 4, R = words / W, E = LB / eb;
     const long long wave_cap = (long long)R * kWave * E;   // elements one wavefront can hold
+    if (LB == 4 && HW > wave_cap) return;              // 4-byte loads only for small planes
     const int ips = N / K;
     f->LB = LB;
     if (HW <= wave_cap) {
         f->LPP = (int)((HW + (long long)kWave * E - 1) / ((long long)kWave * E));
         // register slots per plane: the smallest instantiated count that holds a plane and
         // leaves at most 16 planes per wavefront
-        static const int kSlotCounts[] = {2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 64};
+        static const int kSlotCounts[] = {2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 64, 128};
         int lppc = 0;
         for (int cand : kSlotCounts)
             if (cand >= f->LPP && cand * 16 >= R && cand <= R) { lppc = cand; break; }

@@ -133,6 +133,15 @@ template <> struct Words<8> {
     }
 };
 
+template <> struct Words<4> {
+    static __device__ __forceinline__ void load(const void* p, uint32_t* d) { d[0] = *reinterpret_cast<const uint32_t*>(p); }
+    static __device__ __forceinline__ void store(void* p, const uint32_t* d, int nt)
+    {
+        if (nt) __builtin_nontemporal_store(d[0], reinterpret_cast<uint32_t*>(p));
+        else *reinterpret_cast<uint32_t*>(p) = d[0];
+    }
+};
+
 // Unit data beyond the registers: slot j of thread t lives at ext[(j*256 + t)*4 ..+4).
 // A wavefront fills its 64 consecutive entries of a slot with one global-to-LDS
 // load (consecutive lanes write consecutive 16 bytes), so the data never passes

@@ -81,6 +81,12 @@ SMALL = [
     ("nchw-f32-plane7938-8mod16", dict(N=4, C=3, H=63, W=126, K=2, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane84-8mod16", dict(N=6, C=4, H=6, W=14, K=2, layout="NCHW", dtype="bf16")),
     ("nchw-bf16-plane4100-8mod16", dict(N=4, C=3, H=50, W=82, K=4, layout="NCHW", dtype="bf16")),
+    # small planes whose byte size is not a multiple of 8 (4-byte accesses in the single-launch kernels)
+    ("nchw-f32-plane1075-odd", dict(N=8, C=6, H=25, W=43, K=4, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane15-odd", dict(N=6, C=5, H=3, W=5, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane8181-odd", dict(N=4, C=3, H=81, W=101, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane1050", dict(N=8, C=12, H=25, W=42, K=4, layout="NCHW", dtype="bf16")),
+    ("nchw-bf16-plane6-", dict(N=4, C=3, H=2, W=3, K=2, layout="NCHW", dtype="bf16")),
     # large planes: tiles that spill past the registers into LDS slots, ragged last tile
     ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),

@@ -345,6 +345,23 @@ __device__ __forceinline__ void reduce_rows(const FusedArgs& A, int c, ReduceLds
 }
 
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
+// A per-channel constant as a scalar register.  Besides saving a vector register this makes
+// the compiler wait for the constant's load HERE: left in a vector register, a value loaded
+// from memory shortly before the write-out loop makes it put a full `s_waitcnt vmcnt(0)` in
+// front of every slot of that loop (each slot is a block that may be skipped, so it cannot
+// count the stores in between), and each store then waits for the one before it.
+__device__ __forceinline__ float uniform_f(float v)
+{
+    return __uint_as_float((unsigned)__builtin_amdgcn_readfirstlane((int)__float_as_uint(v)));
+}
+// A per-channel input (gamma, beta; mean, invstd in the backward) read through the scalar
+// unit: nothing in the launch writes these arrays, so they may be read as constant memory,
+// and a scalar load does not queue up behind the unit's vector loads and stores.
+__device__ __forceinline__ float load_scalar(const float* p, int i)
+{
+    typedef const float __attribute__((address_space(4))) const_float;
+    return *reinterpret_cast<const_float*>(reinterpret_cast<uintptr_t>(p + uniform(i)));
+}
 
 // keeps the compiler from carrying per-slot addresses from one pass over the
 // registers to the next (they are cheap to recompute and would cost dozens of VGPRs)
@@ -524,8 +541,8 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             reduce_rows<1, ST_MEAN>(A, c, lds, (double)pivot, g.u == 0);
         }
         CGBN_STAMP(3);
-        float mu = lds.stat[0];
-        const float mulo = lds.stat[1];
+        float mu = uniform_f(lds.stat[0]);
+        const float mulo = uniform_f(lds.stat[1]);
         if (!ok1) mu = __uint_as_float(0x7fc00000u);
         if (g.u == 0 && t == 0) {
             A.mean[c] = mu;
@@ -592,7 +609,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             reduce_rows<1, ST_INVSTD>(A, c, lds, 0.0, g.u == 0, 1);
         }
         CGBN_STAMP(6);
-        float istd = lds.stat[0];
+        float istd = uniform_f(lds.stat[0]);
         if (!ok1 || !ok2) istd = __uint_as_float(0x7fc00000u);
         if (g.u == 0 && t == 0) A.invstd[c] = istd;
 
@@ -601,7 +618,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             // with a shortcut: its slots are fetched kBatch at a time, just before they are used
             constexpr int kBatch = 16 / W;
             const unsigned loff = SL::lane_offset(t);
-            const float gsc = A.gamma[c] * istd, bsh = A.beta[c];
+            const float gsc = A.gamma[c] * istd, bsh = A.beta[c];     // (as scalars: measured 25 % slower here)
             const char* ru = static_cast<const char*>(A.aux) + g.base;
 #pragma unroll
             for (int s0 = 0; s0 < RT; s0 += kBatch) {
@@ -641,7 +658,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             }
         } else {
             const unsigned loff = SL::lane_offset(t);
-            const float gsc = A.gamma[c] * istd, bsh = A.beta[c];
+            const float gsc = uniform_f(load_scalar(A.gamma, c) * istd), bsh = load_scalar(A.beta, c);
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
@@ -704,6 +721,8 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
         const char* xu = xb + g.base;
         const char* gu = gb + g.base;
         char* ou = ob + g.base;
+        // (vector registers on purpose: as scalars these constants cost the small-plane variants scalar-register
+        // spills inside the slot loops, and the large-plane variants gain nothing from unthrottled dx stores)
         const float mu = A.mean[c];
         const float mulo = A.mean_lo ? A.mean_lo[c] : 0.f;
         const float istd = A.invstd[c];

@@ -15,22 +15,28 @@
 // The NCHW single-launch kernels are instantiated in cgbn_fused_inst.hip (one translation
 // unit per element type, direction and activation); here they are only declared.
 namespace cgbn {
-#define CGBN_DECL_F(LB_, LPPC_)                                                               \
-    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 0>(FusedArgs);     \
-    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 1>(FusedArgs);     \
-    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 2>(FusedArgs);     \
-    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 2>(FusedArgs);    \
-    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 0>(FusedArgs);    \
-    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 1>(FusedArgs);
-#define CGBN_DECL_B(LB_, LPPC_)                                                               \
-    extern template __global__ void nchw_fused_backward<float, LB_, LPPC_, 0>(FusedArgs);    \
-    extern template __global__ void nchw_fused_backward<float, LB_, LPPC_, 1>(FusedArgs);    \
-    extern template __global__ void nchw_fused_backward<bf16_t, LB_, LPPC_, 0>(FusedArgs);   \
-    extern template __global__ void nchw_fused_backward<bf16_t, LB_, LPPC_, 1>(FusedArgs);
+#define CGBN_DECL_FX(LB_, LPPC_, BIG_)                                                              \
+    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 0, BIG_>(FusedArgs);     \
+    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 1, BIG_>(FusedArgs);     \
+    extern template __global__ void nchw_fused_forward<float, LB_, LPPC_, 2, BIG_>(FusedArgs);     \
+    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 2, BIG_>(FusedArgs);    \
+    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 0, BIG_>(FusedArgs);    \
+    extern template __global__ void nchw_fused_forward<bf16_t, LB_, LPPC_, 1, BIG_>(FusedArgs);
+#define CGBN_DECL_BX(LB_, LPPC_, BIG_)                                                              \
+    extern template __global__ void nchw_fused_backward<float, LB_, LPPC_, 0, BIG_>(FusedArgs);    \
+    extern template __global__ void nchw_fused_backward<float, LB_, LPPC_, 1, BIG_>(FusedArgs);    \
+    extern template __global__ void nchw_fused_backward<bf16_t, LB_, LPPC_, 0, BIG_>(FusedArgs);   \
+    extern template __global__ void nchw_fused_backward<bf16_t, LB_, LPPC_, 1, BIG_>(FusedArgs);
+#define CGBN_DECL_F(LB_, LPPC_) CGBN_DECL_FX(LB_, LPPC_, 0)
+#define CGBN_DECL_B(LB_, LPPC_) CGBN_DECL_BX(LB_, LPPC_, 0)
 CGBN_FUSED_COMMON(CGBN_DECL_F)
 CGBN_FUSED_FORWARD_ONLY(CGBN_DECL_F)
 CGBN_FUSED_COMMON(CGBN_DECL_B)
 CGBN_FUSED_BACKWARD_ONLY(CGBN_DECL_B)
+CGBN_DECL_FX(16, 0, 1)
+CGBN_DECL_BX(16, 0, 1)
+#undef CGBN_DECL_FX
+#undef CGBN_DECL_BX
 #undef CGBN_DECL_F
 #undef CGBN_DECL_B
 }  // namespace cgbn
@@ -50,6 +56,7 @@ struct Tuning {
     long long fused = 1;                 // register-resident single-launch path where the shape allows it
     long long spin_limit = 1LL << 24;    // polls of a bounded wait in the fused kernels before it gives up
     long long cooperative = 0;           // launch the single-launch kernels cooperatively (co-residency guaranteed by the runtime)
+    long long big_lds = 1;               // large planes with few rows/shards: keep more unit data in LDS
     long long one_sweep_stats = 0;       // forward statistics in one sweep (a variant, not Algorithm 1's two passes)
     long long fused_groups = 0;          // workgroups of the fused grid (0 = as many as are resident at once)
 };
@@ -66,6 +73,7 @@ struct FusedPlan {
     int LB;               // bytes per load: 16 or 8
     int LPPC;             // 0: large planes; else register slots per plane (an instantiated count >= LPP)
     int tp, TL, LPP, IPU, U, rows, rps, G;
+    int big;              // large planes: the variant that stages few rows and keeps more unit data in LDS
     long long total_units;
 };
 
@@ -91,7 +99,8 @@ struct Plan {
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words, FusedPlan* f)
+void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words, int lds_words_big,
+                     FusedPlan* f)
 {
     std::memset(f, 0, sizeof(*f));
     if (K > kFusedMaxShards) return;
@@ -123,19 +132,26 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
         f->rows = N;
         f->rps = ips;
     } else {
-        // large planes: a tile also fills the LDS slots (16-byte loads only)
-        const long long cap = wave_cap * 4 + (LB == 16 ? (long long)(lds_words / W) * kThreads * E : 0);
-        long long tp = (HW + cap - 1) / cap;
-        long long gran = (long long)kThreads * E;
-        long long TL = (HW + tp - 1) / tp;
-        TL = (TL + gran - 1) / gran * gran;
-        tp = (HW + TL - 1) / TL;
-        if ((long long)N * tp > kFusedMaxRows) return;
-        f->tp = (int)tp;
-        f->TL = (int)TL;
-        f->U = (int)(N * tp);
-        f->rows = f->U;
-        f->rps = (int)(ips * tp);
+        // large planes: a tile also fills the LDS slots (16-byte loads only); with few rows and shards to
+        // stage, the variant with more LDS slots is taken
+        const long long gran = (long long)kThreads * E;
+        for (int big = (LB == 16 && g_tune.big_lds && K <= kFusedMaxShardsBig) ? 1 : 0; big >= 0; --big) {
+            const int lw = big ? lds_words_big : lds_words;
+            const long long cap = wave_cap * 4 + (LB == 16 ? (long long)(lw / W) * kThreads * E : 0);
+            long long tp = (HW + cap - 1) / cap;
+            long long TL = (HW + tp - 1) / tp;
+            TL = (TL + gran - 1) / gran * gran;
+            tp = (HW + TL - 1) / TL;
+            if (big && (long long)N * tp > kFusedMaxRowsBig) continue;
+            if ((long long)N * tp > kFusedMaxRows) return;
+            f->big = big;
+            f->tp = (int)tp;
+            f->TL = (int)TL;
+            f->U = (int)(N * tp);
+            f->rows = f->U;
+            f->rps = (int)(ips * tp);
+            break;
+        }
     }
     if (f->rows > kFusedMaxRows) return;
     f->total_units = (long long)C * f->U;
@@ -266,8 +282,8 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     int G = 1;
     while (G < kWave && G < p->rps) G <<= 1;
     p->G = G;
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, &p->ff);
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, &p->fb);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, &p->ff);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, &p->fb);
     int max_rows = p->rows;
     if (p->ff.ok && p->ff.rows > max_rows) max_rows = p->ff.rows;
     if (p->fb.ok && p->fb.rows > max_rows) max_rows = p->fb.rows;
@@ -459,10 +475,14 @@ template <typename T, bool FWD, int ACT>
 cgbn_status launch_fused_t(const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st, bool* taken)
 {
     *taken = false;
+    if (f.big && f.LB == 16 && f.LPPC == 0) {
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, 0, ACT, 1>, f, A, sync_words, st, taken);
+        else return launch_fused_kernel(nchw_fused_backward<T, 16, 0, ACT, 1>, f, A, sync_words, st, taken);
+    }
 #define CGBN_FUSED_CASE(LB_, LPPC_)                                                                          \
     if (f.LB == LB_ && f.LPPC == LPPC_) {                                                                    \
-        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT>, f, A, sync_words, st, taken); \
-        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT>, f, A, sync_words, st, taken); \
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 0>, f, A, sync_words, st, taken); \
+        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 0>, f, A, sync_words, st, taken); \
     }
     CGBN_FUSED_COMMON(CGBN_FUSED_CASE)
     if constexpr (FWD) {
@@ -876,6 +896,7 @@ static long long* tuning_slot(const char* key)
     if (!std::strcmp(key, "fused_groups")) return &g_tune.fused_groups;
     if (!std::strcmp(key, "one_sweep_stats")) return &g_tune.one_sweep_stats;
     if (!std::strcmp(key, "cooperative")) return &g_tune.cooperative;
+    if (!std::strcmp(key, "big_lds")) return &g_tune.big_lds;
     return nullptr;
 }
 
@@ -884,7 +905,7 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
     long long* slot = tuning_slot(key);
     if (!slot) return CGBN_ERR_TUNING;
     if (slot == &g_tune.reverse || slot == &g_tune.nt_store || slot == &g_tune.fused || slot == &g_tune.one_sweep_stats ||
-        slot == &g_tune.cooperative) {
+        slot == &g_tune.cooperative || slot == &g_tune.big_lds) {
         if (value != 0 && value != 1) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.spin_limit) {
         if (value < 0 || value > 0xffffffffLL) return CGBN_ERR_TUNING;

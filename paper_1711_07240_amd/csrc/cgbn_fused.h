@@ -52,6 +52,11 @@ constexpr int kSyncHeader = 64;           // words before the per-channel arrays
 constexpr int kFusedLdsWords = 24;        // further 32-bit words of unit data per thread kept in LDS (large planes, 16-byte loads)
 constexpr int kFusedMaxRows = 2048;       // rows of a channel staged in LDS by the reducing workgroup
 constexpr int kFusedMaxShards = 512;
+// Channels with few rows and shards leave most of that staging area unused: the "big"
+// variants of the large-plane kernels stage at most these and give the LDS to unit data.
+constexpr int kFusedLdsWordsBig = 48;
+constexpr int kFusedMaxRowsBig = 384;
+constexpr int kFusedMaxShardsBig = 48;
 
 // Optional per-unit timestamps for performance work (off in the product build).
 #ifdef CGBN_TRACE
@@ -209,9 +214,9 @@ __device__ __forceinline__ void publish_row(float* p, float v)
 }
 
 // LDS of a workgroup gathering and reducing a channel's rows
-struct ReduceLds {
-    float rows[2][kFusedMaxRows];
-    double shard[2][kFusedMaxShards];
+template <int BIG> struct ReduceLdsT {
+    float rows[2][BIG ? kFusedMaxRowsBig : kFusedMaxRows];
+    double shard[2][BIG ? kFusedMaxShardsBig : kFusedMaxShards];
     float stat[2];        // the reduced statistics, broadcast to the workgroup
     int missing;          // some row was still the sentinel in this poll
 };
@@ -249,9 +254,9 @@ __device__ __forceinline__ void count_in(unsigned* cnt, unsigned* flag, int U)
 // still be in flight when the flag is seen).
 // Bounded: false if `spin_limit` polls were not enough.
 // Row r of the first array is rows0[r * stride] (rows1 likewise, used if Q == 2).
-template <int Q>
+template <int Q, class LDS>
 __device__ __forceinline__ bool gather_rows(const FusedArgs& A, const float* rows0, const float* rows1, int stride,
-                                            const unsigned* flag, ReduceLds& L)
+                                            const unsigned* flag, LDS& L)
 {
     const int t = threadIdx.x;
     const unsigned* p0 = reinterpret_cast<const unsigned*>(rows0);
@@ -295,8 +300,8 @@ __device__ __forceinline__ bool gather_rows(const FusedArgs& A, const float* row
 // precision, fixed order, the same in every workgroup.  Lane 0 turns the totals
 // into the statistics (MODE) and leaves them in L.stat[] as floats; shard sums go
 // to sh0/sh1 if `write_shards`.
-template <int Q, int MODE>
-__device__ __forceinline__ void reduce_rows(const FusedArgs& A, int c, ReduceLds& L, double pivot,
+template <int Q, int MODE, class LDS>
+__device__ __forceinline__ void reduce_rows(const FusedArgs& A, int c, LDS& L, double pivot,
                                             bool write_shards, int first = 0)
 {
     const double shard_offset0 = pivot * A.shard_count;
@@ -435,16 +440,17 @@ struct Slots {
 // ---------------------------------------------------------------------------
 // ACT == 1: y = max(0, step 11).  ACT == 2: y = max(0, step 11 + shortcut), the shortcut
 // (A.aux) being read a few slots at a time while the unit is written out.
-template <typename T, int LB, int LPPC, int ACT>
+template <typename T, int LB, int LPPC, int ACT, int BIG>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 {
+    static_assert(BIG == 0 || (LPPC == 0 && LB == 16), "the big-LDS variant exists for large planes with 16-byte loads");
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
     constexpr int R = kFusedWords / W;                                       // slots held in registers
-    constexpr int RL = (LPPC == 0 && LB == 16) ? kFusedLdsWords / W : 0;     // slots held in LDS
+    constexpr int RL = (LPPC == 0 && LB == 16) ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / W : 0;     // slots held in LDS
     constexpr int RT = R + RL;
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
-    __shared__ ReduceLds lds;
+    __shared__ ReduceLdsT<BIG> lds;
     __shared__ float s_red[4];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
     const T* x = static_cast<const T*>(A.x);
@@ -694,16 +700,17 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 // ACT != 0: dy is first masked by the stored output (A.aux) being positive.  The output's
 // slots pass through the storage that x takes afterwards, so the unit costs one more round
 // of loads but no more registers; the masked dy also goes to A.out2 if that is not null.
-template <typename T, int LB, int LPPC, int ACT>
+template <typename T, int LB, int LPPC, int ACT, int BIG>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
 {
+    static_assert(BIG == 0 || (LPPC == 0 && LB == 16), "the big-LDS variant exists for large planes with 16-byte loads");
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
     constexpr int R = kFusedWords / 2 / W;       // slots per tensor held in registers
-    constexpr int RL = (LPPC == 0 && LB == 16) ? kFusedLdsWords / 2 / W : 0;   // ... and in LDS
+    constexpr int RL = (LPPC == 0 && LB == 16) ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / 2 / W : 0;   // ... and in LDS
     constexpr int RT = R + RL;
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
-    __shared__ ReduceLds lds;
+    __shared__ ReduceLdsT<BIG> lds;
     __shared__ float s_red[8];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
     const char* xb = static_cast<const char*>(A.x);

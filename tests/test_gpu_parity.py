@@ -114,6 +114,24 @@ def test_small_shapes(name, kw):
     run_case(BASE.scaled(name=name, **kw), name)
 
 
+LARGE_PLANES = [c for c in SMALL if c[0] in ("nchw-f32-plane40000", "nchw-f32-plane77500", "nchw-bf16-plane90000",
+                                              "nchw-f32-block-ragged", "nchw-bf16-block")]
+
+
+@pytest.mark.parametrize("name,kw", LARGE_PLANES, ids=[s[0] for s in LARGE_PLANES])
+def test_large_planes_without_the_big_lds_variant(name, kw, path):
+    """Large planes with few rows take the variant that keeps more unit data in LDS; this runs the same
+    shapes through the ordinary variant (the one shapes with many rows or shards use)."""
+    if path == 0:
+        pytest.skip("multi-sweep path: no such variant")
+    assert len(LARGE_PLANES) == 5
+    L.cgbn_set_tuning("big_lds", 0)
+    try:
+        run_case(BASE.scaled(name=name, **kw), name + " (ordinary LDS split)")
+    finally:
+        L.cgbn_set_tuning("big_lds", 1)
+
+
 @pytest.mark.parametrize("kind", ["relu", "offset-f32", "offset-bf16"])
 def test_value_distributions_small(kind):
     if kind == "relu":

@@ -229,8 +229,9 @@ const char* cgbn_status_string(cgbn_status status);
  *   "cooperative"      0/1 (default 0): launch the single-launch kernels cooperatively, so that the runtime
  *                      guarantees the whole grid is resident; needed only if such calls can overlap on
  *                      different streams; costs about 15 us per launch
- *   "big_lds"          0/1 (default 1): large NCHW planes with at most 384 rows and 48 shards use the variant of
- *                      the single-launch kernels that stages few rows and keeps more unit data in LDS
+ *   "big_lds"          0/1 (default 1): NCHW shapes with at most 384 rows and 48 (large planes) or 128 (small
+ *                      planes) shards use variants of the single-launch kernels that stage few rows and keep
+ *                      more unit data in LDS
  *   "fused_groups"     workgroups of that launch (0 = all that are resident at once)
  *   "spin_limit"       polls before a device-side wait gives up
  * cgbn_get_tuning returns -1 for an unknown key. */

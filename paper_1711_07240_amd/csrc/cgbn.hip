@@ -35,6 +35,12 @@ CGBN_FUSED_COMMON(CGBN_DECL_B)
 CGBN_FUSED_BACKWARD_ONLY(CGBN_DECL_B)
 CGBN_DECL_FX(16, 0, 1)
 CGBN_DECL_BX(16, 0, 1)
+#define CGBN_DECL_F2(LB_, LPPC_) CGBN_DECL_FX(LB_, LPPC_, 2)
+#define CGBN_DECL_B2(LB_, LPPC_) CGBN_DECL_BX(LB_, LPPC_, 2)
+CGBN_FUSED_BIG_SMALL(CGBN_DECL_F2)
+CGBN_FUSED_BIG_SMALL(CGBN_DECL_B2)
+#undef CGBN_DECL_F2
+#undef CGBN_DECL_B2
 #undef CGBN_DECL_FX
 #undef CGBN_DECL_BX
 #undef CGBN_DECL_F
@@ -73,7 +79,7 @@ struct FusedPlan {
     int LB;               // bytes per load: 16 or 8
     int LPPC;             // 0: large planes; else register slots per plane (an instantiated count >= LPP)
     int tp, TL, LPP, IPU, U, rows, rps, G;
-    int big;              // large planes: the variant that stages few rows and keeps more unit data in LDS
+    int big;              // 1 (large planes) / 2 (small planes): the variant that stages few rows and keeps more unit data in LDS
     long long total_units;
 };
 
@@ -100,7 +106,7 @@ struct Plan {
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words, int lds_words_big,
-                     FusedPlan* f)
+                     int lds_words_big_small, FusedPlan* f)
 {
     std::memset(f, 0, sizeof(*f));
     if (K > kFusedMaxShards) return;
@@ -124,7 +130,17 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
             if (cand >= f->LPP && cand * 16 >= R && cand <= R) { lppc = cand; break; }
         if (!lppc) return;
         f->LPPC = lppc;
-        int per_unit = 4 * (R / lppc);
+        // with few rows and shards to stage, further whole planes per wavefront go to LDS
+        int lds_planes = 0;
+        if (g_tune.big_lds && LB >= 8 && N <= kFusedMaxRowsBig && K <= kFusedMaxShardsBigSmall) {
+            bool built = false;
+#define CGBN_IS_BUILT(LB_, LPPC_) built = built || (LB == LB_ && lppc == LPPC_);
+            CGBN_FUSED_BIG_SMALL(CGBN_IS_BUILT)
+#undef CGBN_IS_BUILT
+            if (built) lds_planes = (lds_words_big_small / W) / lppc;
+        }
+        f->big = lds_planes > 0 ? 2 : 0;
+        int per_unit = 4 * (R / lppc + lds_planes);
         f->U = (N + per_unit - 1) / per_unit;
         f->IPU = (N + f->U - 1) / f->U;
         // byte offsets inside a unit are 32-bit
@@ -282,8 +298,8 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     int G = 1;
     while (G < kWave && G < p->rps) G <<= 1;
     p->G = G;
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, &p->ff);
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, &p->fb);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, kFusedLdsWordsBigSmall, &p->ff);
+    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, kFusedLdsWordsBigSmall / 2, &p->fb);
     int max_rows = p->rows;
     if (p->ff.ok && p->ff.rows > max_rows) max_rows = p->ff.rows;
     if (p->fb.ok && p->fb.rows > max_rows) max_rows = p->fb.rows;
@@ -479,6 +495,13 @@ cgbn_status launch_fused_t(const FusedPlan& f, FusedArgs& A, int sync_words, hip
         if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, 0, ACT, 1>, f, A, sync_words, st, taken);
         else return launch_fused_kernel(nchw_fused_backward<T, 16, 0, ACT, 1>, f, A, sync_words, st, taken);
     }
+#define CGBN_FUSED_CASE2(LB_, LPPC_)                                                                         \
+    if (f.big == 2 && f.LB == LB_ && f.LPPC == LPPC_) {                                                      \
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 2>, f, A, sync_words, st, taken); \
+        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 2>, f, A, sync_words, st, taken); \
+    }
+    CGBN_FUSED_BIG_SMALL(CGBN_FUSED_CASE2)
+#undef CGBN_FUSED_CASE2
 #define CGBN_FUSED_CASE(LB_, LPPC_)                                                                          \
     if (f.LB == LB_ && f.LPPC == LPPC_) {                                                                    \
         if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 0>, f, A, sync_words, st, taken); \

@@ -57,6 +57,9 @@ constexpr int kFusedMaxShards = 512;
 constexpr int kFusedLdsWordsBig = 48;
 constexpr int kFusedMaxRowsBig = 384;
 constexpr int kFusedMaxShardsBig = 48;
+// The same for small planes (BIG == 2): whole further planes per wavefront live in LDS.
+constexpr int kFusedLdsWordsBigSmall = 44;
+constexpr int kFusedMaxShardsBigSmall = 128;
 
 // Optional per-unit timestamps for performance work (off in the product build).
 #ifdef CGBN_TRACE
@@ -147,27 +150,62 @@ template <> struct Words<4> {
     }
 };
 
-// Unit data beyond the registers: slot j of thread t lives at ext[(j*256 + t)*4 ..+4).
-// A wavefront fills its 64 consecutive entries of a slot with one global-to-LDS
-// load (consecutive lanes write consecutive 16 bytes), so the data never passes
-// through registers on its way in.
-__device__ __forceinline__ void lds_slot_fill(const char* gaddr, uint32_t* ext, int j, int w)
-{
-    __builtin_amdgcn_global_load_lds(
-        (const void __attribute__((address_space(1)))*)gaddr,
-        (void __attribute__((address_space(3)))*)(ext + ((size_t)j * kThreads + (size_t)w * kWave) * 4), 16, 0, 0);
-}
-__device__ __forceinline__ void lds_slot_read(const uint32_t* ext, int j, int t, uint32_t* out)
-{
-    u32x4 v = *reinterpret_cast<const u32x4*>(ext + ((size_t)j * kThreads + t) * 4);
-    out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
-}
-
-__device__ __forceinline__ void lds_slot_write(uint32_t* ext, int j, int t, const uint32_t* in)
-{
-    u32x4 v = {in[0], in[1], in[2], in[3]};
-    *reinterpret_cast<u32x4*>(ext + ((size_t)j * kThreads + t) * 4) = v;
-}
+// Unit data beyond the registers: slot j of thread t lives at byte (j*256 + t)*LB of `ext`,
+// i.e. a wavefront's part of a slot is a linear image of 64*LB bytes of global memory.  It
+// is filled by global-to-LDS loads, so the data never passes through registers on its way
+// in: one 16-byte load per lane (LB == 16), or two 4-byte loads per lane for the two halves
+// of the wavefront's 512 bytes (LB == 8; there is no 8-byte global-to-LDS load).
+//   lane_src  this lane's own LB bytes in global memory (what a register slot would load)
+//   wave_src  the first byte of the wavefront's part of the slot (uniform)
+//   valid     bytes of that part that belong to the unit (uniform); lanes past it re-read its start
+template <int LB> struct LdsSlot;
+template <> struct LdsSlot<16> {
+    static __device__ __forceinline__ void fill(const char* lane_src, const char*, unsigned, uint32_t* ext, int j, int w, int)
+    {
+        __builtin_amdgcn_global_load_lds(
+            (const void __attribute__((address_space(1)))*)lane_src,
+            (void __attribute__((address_space(3)))*)(ext + ((size_t)j * kThreads + (size_t)w * kWave) * 4), 16, 0, 0);
+    }
+    static __device__ __forceinline__ void read(const uint32_t* ext, int j, int t, uint32_t* out)
+    {
+        u32x4 v = *reinterpret_cast<const u32x4*>(ext + ((size_t)j * kThreads + t) * 4);
+        out[0] = v.x; out[1] = v.y; out[2] = v.z; out[3] = v.w;
+    }
+    static __device__ __forceinline__ void write(uint32_t* ext, int j, int t, const uint32_t* in)
+    {
+        u32x4 v = {in[0], in[1], in[2], in[3]};
+        *reinterpret_cast<u32x4*>(ext + ((size_t)j * kThreads + t) * 4) = v;
+    }
+};
+template <> struct LdsSlot<8> {
+    static __device__ __forceinline__ void fill(const char*, const char* wave_src, unsigned valid, uint32_t* ext, int j, int w,
+                                                int lane)
+    {
+        uint32_t* dst = ext + ((size_t)j * kThreads + (size_t)w * kWave) * 2;
+        unsigned l4 = (unsigned)lane * 4u;
+        asm volatile("" : "+v"(l4));       // recomputed per slot: carried across slots these offsets would cost dozens of registers
+        const unsigned o0 = l4, o1 = 256u + l4;
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(wave_src + (o0 < valid ? o0 : 0u)),
+                                         (void __attribute__((address_space(3)))*)dst, 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(wave_src + (o1 < valid ? o1 : 0u)),
+                                         (void __attribute__((address_space(3)))*)(dst + 64), 4, 0, 0);
+    }
+    static __device__ __forceinline__ void read(const uint32_t* ext, int j, int t, uint32_t* out)
+    {
+        u32x2 v = *reinterpret_cast<const u32x2*>(ext + ((size_t)j * kThreads + t) * 2);
+        out[0] = v.x; out[1] = v.y;
+    }
+    static __device__ __forceinline__ void write(uint32_t* ext, int j, int t, const uint32_t* in)
+    {
+        u32x2 v = {in[0], in[1]};
+        *reinterpret_cast<u32x2*>(ext + ((size_t)j * kThreads + t) * 2) = v;
+    }
+};
+template <> struct LdsSlot<4> {      // never used: 4-byte variants keep everything in registers
+    static __device__ __forceinline__ void fill(const char*, const char*, unsigned, uint32_t*, int, int, int) {}
+    static __device__ __forceinline__ void read(const uint32_t*, int, int, uint32_t* out) { out[0] = 0u; }
+    static __device__ __forceinline__ void write(uint32_t*, int, int, const uint32_t*) {}
+};
 
 // the elements packed in one 32-bit register
 template <typename T> struct Packed;
@@ -216,7 +254,7 @@ __device__ __forceinline__ void publish_row(float* p, float v)
 // LDS of a workgroup gathering and reducing a channel's rows
 template <int BIG> struct ReduceLdsT {
     float rows[2][BIG ? kFusedMaxRowsBig : kFusedMaxRows];
-    double shard[2][BIG ? kFusedMaxShardsBig : kFusedMaxShards];
+    double shard[2][BIG == 2 ? kFusedMaxShardsBigSmall : BIG == 1 ? kFusedMaxShardsBig : kFusedMaxShards];
     float stat[2];        // the reduced statistics, broadcast to the workgroup
     int missing;          // some row was still the sentinel in this poll
 };
@@ -433,6 +471,17 @@ struct Slots {
         return (unsigned)slot_offset(s) + loff < (unsigned)g.len;
     }
     static constexpr bool ends_plane(int s) { return SMALL && (s % SPP) == SPP - 1; }
+    // For LDS slots: byte offset (from the unit's base) of the part of slot s that wavefront w fills, and how
+    // many bytes of that part belong to the unit (both uniform)
+    static __device__ __forceinline__ size_t wave_base(const FusedArgs& A, int s, int w)
+    {
+        return plane_base(A, s, w) + (size_t)slot_offset(s) + (SMALL ? 0 : (size_t)w * (kWave * LB));
+    }
+    static __device__ __forceinline__ unsigned wave_valid(const UnitGeom& g, int s, int w)
+    {
+        const int left = g.len - slot_offset(s) - (SMALL ? 0 : w * (kWave * LB));
+        return left > 0 ? (unsigned)left : 0u;
+    }
 };
 
 // ---------------------------------------------------------------------------
@@ -443,13 +492,17 @@ struct Slots {
 template <typename T, int LB, int LPPC, int ACT, int BIG>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 {
-    static_assert(BIG == 0 || (LPPC == 0 && LB == 16), "the big-LDS variant exists for large planes with 16-byte loads");
+    static_assert(BIG == 0 || (BIG == 1 && LPPC == 0 && LB == 16) || (BIG == 2 && LPPC > 0 && LB >= 8),
+                  "BIG 1: large planes with 16-byte loads; BIG 2: small planes with 8- or 16-byte loads");
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
-    constexpr int R = kFusedWords / W;                                       // slots held in registers
-    constexpr int RL = (LPPC == 0 && LB == 16) ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / W : 0;     // slots held in LDS
-    constexpr int RT = R + RL;
+    constexpr int R = kFusedWords / W;                                       // slots the registers offer
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
+    constexpr int RS = SMALL ? (R / LPPC) * LPPC : R;                        // register slots in use (whole planes)
+    // slots held in LDS: large planes with 16-byte loads; small planes (BIG == 2): whole planes
+    constexpr int RL = SMALL ? (BIG == 2 ? (kFusedLdsWordsBigSmall / W / LPPC) * LPPC : 0)
+                             : (LB == 16 ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / W : 0);
+    constexpr int RT = RS + RL;
     __shared__ ReduceLdsT<BIG> lds;
     __shared__ float s_red[4];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
@@ -481,8 +534,8 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                     // lanes past the end re-read the slot's first bytes; they are masked later
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
                     const char* src = xu + SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
-                    if (s < R) Words<LB>::load(src, &d[(s < R ? s : 0) * W]);
-                    else lds_slot_fill(src, ext, s - R, w);
+                    if (s < RS) Words<LB>::load(src, &d[(s < RS ? s : 0) * W]);
+                    else LdsSlot<LB>::fill(src, xu + SL::wave_base(A, s, w), SL::wave_valid(g, s, w), ext, s - RS, w, lane);
                 }
             }
             if (RL > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the LDS slots have landed
@@ -496,11 +549,11 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t wv[W];
-                    if (s < R) {
+                    if (s < RS) {
 #pragma unroll
-                        for (int q = 0; q < W; ++q) wv[q] = d[(s < R ? s : 0) * W + q];
+                        for (int q = 0; q < W; ++q) wv[q] = d[(s < RS ? s : 0) * W + q];
                     } else {
-                        lds_slot_read(ext, s - R, t, wv);
+                        LdsSlot<LB>::read(ext, s - RS, t, wv);
                     }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
@@ -564,11 +617,11 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t wv[W];
-                    if (s < R) {
+                    if (s < RS) {
 #pragma unroll
-                        for (int q = 0; q < W; ++q) wv[q] = d[(s < R ? s : 0) * W + q];
+                        for (int q = 0; q < W; ++q) wv[q] = d[(s < RS ? s : 0) * W + q];
                     } else {
-                        lds_slot_read(ext, s - R, t, wv);
+                        LdsSlot<LB>::read(ext, s - RS, t, wv);
                     }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
@@ -640,11 +693,11 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                     const int s = s0 + j;
                     if (s < RT && SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                         uint32_t o[W], wv[W];
-                        if (s < R) {
+                        if (s < RS) {
 #pragma unroll
-                            for (int q = 0; q < W; ++q) wv[q] = d[(s < R ? s : 0) * W + q];
+                            for (int q = 0; q < W; ++q) wv[q] = d[(s < RS ? s : 0) * W + q];
                         } else {
-                            lds_slot_read(ext, s - R, t, wv);
+                            LdsSlot<LB>::read(ext, s - RS, t, wv);
                         }
 #pragma unroll
                         for (int q = 0; q < W; ++q) {
@@ -669,11 +722,11 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t o[W], wv[W];
-                    if (s < R) {
+                    if (s < RS) {
 #pragma unroll
-                        for (int q = 0; q < W; ++q) wv[q] = d[(s < R ? s : 0) * W + q];
+                        for (int q = 0; q < W; ++q) wv[q] = d[(s < RS ? s : 0) * W + q];
                     } else {
-                        lds_slot_read(ext, s - R, t, wv);
+                        LdsSlot<LB>::read(ext, s - RS, t, wv);
                     }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
@@ -703,13 +756,16 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 template <typename T, int LB, int LPPC, int ACT, int BIG>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
 {
-    static_assert(BIG == 0 || (LPPC == 0 && LB == 16), "the big-LDS variant exists for large planes with 16-byte loads");
+    static_assert(BIG == 0 || (BIG == 1 && LPPC == 0 && LB == 16) || (BIG == 2 && LPPC > 0 && LB >= 8),
+                  "BIG 1: large planes with 16-byte loads; BIG 2: small planes with 8- or 16-byte loads");
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
-    constexpr int R = kFusedWords / 2 / W;       // slots per tensor held in registers
-    constexpr int RL = (LPPC == 0 && LB == 16) ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / 2 / W : 0;   // ... and in LDS
-    constexpr int RT = R + RL;
+    constexpr int R = kFusedWords / 2 / W;       // slots per tensor the registers offer
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
+    constexpr int RS = SMALL ? (R / LPPC) * LPPC : R;                        // register slots in use (whole planes)
+    constexpr int RL = SMALL ? (BIG == 2 ? (kFusedLdsWordsBigSmall / 2 / W / LPPC) * LPPC : 0)
+                             : (LB == 16 ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / 2 / W : 0);   // ... and in LDS
+    constexpr int RT = RS + RL;
     __shared__ ReduceLdsT<BIG> lds;
     __shared__ float s_red[8];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
@@ -744,12 +800,12 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                 if (SL::in_use(A, g, s, w)) {
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
                     size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
-                    if (s < R) {
-                        Words<LB>::load(gu + o, &gd[(s < R ? s : 0) * W]);
-                        Words<LB>::load(yu + o, &xd[(s < R ? s : 0) * W]);
+                    if (s < RS) {
+                        Words<LB>::load(gu + o, &gd[(s < RS ? s : 0) * W]);
+                        Words<LB>::load(yu + o, &xd[(s < RS ? s : 0) * W]);
                     } else {
-                        lds_slot_fill(gu + o, ext, s - R, w);
-                        lds_slot_fill(yu + o, ext, RL + s - R, w);
+                        LdsSlot<LB>::fill(gu + o, gu + SL::wave_base(A, s, w), SL::wave_valid(g, s, w), ext, s - RS, w, lane);
+                        LdsSlot<LB>::fill(yu + o, yu + SL::wave_base(A, s, w), SL::wave_valid(g, s, w), ext, RL + s - RS, w, lane);
                     }
                 }
             }
@@ -757,17 +813,17 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w)) {
-                    if (s < R) {
+                    if (s < RS) {
 #pragma unroll
                         for (int q = 0; q < W; ++q)
-                            gd[(s < R ? s : 0) * W + q] = mask_by_positive<T>(gd[(s < R ? s : 0) * W + q], xd[(s < R ? s : 0) * W + q]);
+                            gd[(s < RS ? s : 0) * W + q] = mask_by_positive<T>(gd[(s < RS ? s : 0) * W + q], xd[(s < RS ? s : 0) * W + q]);
                     } else if (RL > 0) {
-                        uint32_t wg[4], wy[4];
-                        lds_slot_read(ext, s - R, t, wg);
-                        lds_slot_read(ext, RL + s - R, t, wy);
+                        uint32_t wg[W], wy[W];
+                        LdsSlot<LB>::read(ext, s - RS, t, wg);
+                        LdsSlot<LB>::read(ext, RL + s - RS, t, wy);
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) wg[q] = mask_by_positive<T>(wg[q], wy[q]);
-                        lds_slot_write(ext, s - R, t, wg);
+                        for (int q = 0; q < W; ++q) wg[q] = mask_by_positive<T>(wg[q], wy[q]);
+                        LdsSlot<LB>::write(ext, s - RS, t, wg);
                     }
                 }
             }
@@ -777,8 +833,8 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                 if (SL::in_use(A, g, s, w)) {
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
                     size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
-                    if (s < R) Words<LB>::load(xu + o, &xd[(s < R ? s : 0) * W]);
-                    else lds_slot_fill(xu + o, ext, RL + s - R, w);
+                    if (s < RS) Words<LB>::load(xu + o, &xd[(s < RS ? s : 0) * W]);
+                    else LdsSlot<LB>::fill(xu + o, xu + SL::wave_base(A, s, w), SL::wave_valid(g, s, w), ext, RL + s - RS, w, lane);
                 }
             }
             if (RL > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -789,12 +845,12 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                 if (SL::in_use(A, g, s, w)) {
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
                     size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
-                    if (s < R) {
-                        Words<LB>::load(gu + o, &gd[(s < R ? s : 0) * W]);
-                        Words<LB>::load(xu + o, &xd[(s < R ? s : 0) * W]);
+                    if (s < RS) {
+                        Words<LB>::load(gu + o, &gd[(s < RS ? s : 0) * W]);
+                        Words<LB>::load(xu + o, &xd[(s < RS ? s : 0) * W]);
                     } else {
-                        lds_slot_fill(gu + o, ext, s - R, w);
-                        lds_slot_fill(xu + o, ext, RL + s - R, w);
+                        LdsSlot<LB>::fill(gu + o, gu + SL::wave_base(A, s, w), SL::wave_valid(g, s, w), ext, s - RS, w, lane);
+                        LdsSlot<LB>::fill(xu + o, xu + SL::wave_base(A, s, w), SL::wave_valid(g, s, w), ext, RL + s - RS, w, lane);
                     }
                 }
             }
@@ -808,12 +864,12 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
             for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t wx[W], wg[W];
-                    if (s < R) {
+                    if (s < RS) {
 #pragma unroll
-                        for (int q = 0; q < W; ++q) { wx[q] = xd[(s < R ? s : 0) * W + q]; wg[q] = gd[(s < R ? s : 0) * W + q]; }
+                        for (int q = 0; q < W; ++q) { wx[q] = xd[(s < RS ? s : 0) * W + q]; wg[q] = gd[(s < RS ? s : 0) * W + q]; }
                     } else {
-                        lds_slot_read(ext, s - R, t, wg);
-                        lds_slot_read(ext, RL + s - R, t, wx);
+                        LdsSlot<LB>::read(ext, s - RS, t, wg);
+                        LdsSlot<LB>::read(ext, RL + s - RS, t, wx);
                     }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {
@@ -888,12 +944,12 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t o[W];
                     uint32_t wx[W], wg[W];
-                    if (s < R) {
+                    if (s < RS) {
 #pragma unroll
-                        for (int q = 0; q < W; ++q) { wx[q] = xd[(s < R ? s : 0) * W + q]; wg[q] = gd[(s < R ? s : 0) * W + q]; }
+                        for (int q = 0; q < W; ++q) { wx[q] = xd[(s < RS ? s : 0) * W + q]; wg[q] = gd[(s < RS ? s : 0) * W + q]; }
                     } else {
-                        lds_slot_read(ext, s - R, t, wg);
-                        lds_slot_read(ext, RL + s - R, t, wx);
+                        LdsSlot<LB>::read(ext, s - RS, t, wg);
+                        LdsSlot<LB>::read(ext, RL + s - RS, t, wx);
                     }
 #pragma unroll
                     for (int q = 0; q < W; ++q) {

@@ -12,3 +12,7 @@
     X(4, 8) X(4, 10) X(4, 12) X(4, 16) X(4, 24) X(4, 32) X(4, 64)
 #define CGBN_FUSED_FORWARD_ONLY(X) X(16, 24) X(16, 32) X(8, 64) X(4, 128)
 #define CGBN_FUSED_BACKWARD_ONLY(X) X(8, 2) X(8, 3) X(4, 4) X(4, 5) X(4, 6)
+
+// Small planes with few rows and shards to stage (BIG == 2): further whole planes per wavefront in LDS.
+// Only slot counts for which at least one plane fits the LDS share of either direction.
+#define CGBN_FUSED_BIG_SMALL(X) X(8, 4) X(8, 5) X(8, 6) X(8, 8) X(8, 10) X(16, 2) X(16, 3) X(16, 4) X(16, 5)

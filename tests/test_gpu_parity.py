@@ -87,6 +87,10 @@ SMALL = [
     ("nchw-f32-plane8181-odd", dict(N=4, C=3, H=81, W=101, K=2, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane1050", dict(N=8, C=12, H=25, W=42, K=4, layout="NCHW", dtype="bf16")),
     ("nchw-bf16-plane6-", dict(N=4, C=3, H=2, W=3, K=2, layout="NCHW", dtype="bf16")),
+    # small planes, enough images per unit that whole planes live in LDS beside those in registers
+    ("nchw-f32-plane1050-n32", dict(N=32, C=6, H=25, W=42, K=8, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane600-n48", dict(N=48, C=3, H=20, W=30, K=4, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane1100-n56", dict(N=56, C=4, H=25, W=44, K=7, layout="NCHW", dtype="bf16")),
     # large planes: tiles that spill past the registers into LDS slots, ragged last tile
     ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),
@@ -115,16 +119,18 @@ def test_small_shapes(name, kw):
 
 
 LARGE_PLANES = [c for c in SMALL if c[0] in ("nchw-f32-plane40000", "nchw-f32-plane77500", "nchw-bf16-plane90000",
-                                              "nchw-f32-block-ragged", "nchw-bf16-block")]
+                                              "nchw-f32-block-ragged", "nchw-bf16-block", "nchw-f32-plane1050-n32",
+                                              "nchw-f32-plane600-n48", "nchw-bf16-plane1100-n56", "nchw-f32-plane1100")]
 
 
 @pytest.mark.parametrize("name,kw", LARGE_PLANES, ids=[s[0] for s in LARGE_PLANES])
 def test_large_planes_without_the_big_lds_variant(name, kw, path):
-    """Large planes with few rows take the variant that keeps more unit data in LDS; this runs the same
-    shapes through the ordinary variant (the one shapes with many rows or shards use)."""
+    """Shapes with few rows and shards take variants that keep more unit data in LDS (more slots of a large
+    plane's tile, or further whole small planes); this runs the same shapes through the ordinary variants
+    (the ones shapes with many rows or shards use)."""
     if path == 0:
         pytest.skip("multi-sweep path: no such variant")
-    assert len(LARGE_PLANES) == 5
+    assert len(LARGE_PLANES) == 9
     L.cgbn_set_tuning("big_lds", 0)
     try:
         run_case(BASE.scaled(name=name, **kw), name + " (ordinary LDS split)")

@@ -36,6 +36,8 @@ CASES = [
     ("nchw-bf16-plane4100-8mod16", dict(N=4, C=3, H=50, W=82, K=4, layout="NCHW", dtype="bf16")),
     ("nchw-f32-plane1075-odd", dict(N=8, C=6, H=25, W=43, K=4, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane1050", dict(N=8, C=12, H=25, W=42, K=4, layout="NCHW", dtype="bf16")),
+    ("nchw-f32-plane1050-n32", dict(N=32, C=6, H=25, W=42, K=8, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane1100-n56", dict(N=56, C=4, H=25, W=44, K=7, layout="NCHW", dtype="bf16")),
     ("nchw-bf16-wave", dict(N=4, C=6, H=33, W=35, K=2, layout="NCHW", dtype="bf16")),
     ("nchw-bf16-block", dict(N=2, C=2, H=160, W=161, K=2, layout="NCHW", dtype="bf16")),
     ("nchw-bf16-plane2600", dict(N=6, C=4, H=50, W=52, K=3, layout="NCHW", dtype="bf16")),
@@ -74,7 +76,7 @@ def _check(got, ref, dtype, what):
 # shapes the single-launch kernels must take when they are switched on
 SINGLE_LAUNCH = {"nchw-f32-plane1050", "nchw-f32-plane600", "nchw-f32-plane40000", "nchw-f32-plane90000-two-tiles",
                  "nchw-bf16-plane2600", "nchw-f32-plane258-8mod16", "nchw-bf16-plane4100-8mod16",
-                 "nchw-f32-plane1075-odd", "nchw-bf16-plane1050"}
+                 "nchw-f32-plane1075-odd", "nchw-bf16-plane1050", "nchw-f32-plane1050-n32", "nchw-bf16-plane1100-n56"}
 
 
 def run_relu_case(wl, what, with_shortcut):

@@ -68,7 +68,8 @@ typedef enum cgbn_status {
     CGBN_ERR_ALIGN = 7,      /* an activation tensor is not 16-byte aligned */
     CGBN_ERR_HIP = 8,        /* the HIP runtime refused a launch */
     CGBN_ERR_TUNING = 9,     /* unknown tuning key or value out of range */
-    CGBN_ERR_MOMENTUM = 10   /* momentum outside [0, 1] */
+    CGBN_ERR_MOMENTUM = 10,  /* momentum outside [0, 1] */
+    CGBN_ERR_ALIAS = 11      /* two outputs that must differ are the same buffer */
 } cgbn_status;
 
 typedef enum cgbn_layout { CGBN_NCHW = 0, CGBN_NHWC = 1 } cgbn_layout;
@@ -122,7 +123,7 @@ cgbn_status cgbn_forward_relu(const void* x, const void* shortcut, int N, int C,
 /* Its backward.  `y` is the output cgbn_forward_relu stored: gradient passes where y > 0
  * (dz = dy there, 0 elsewhere), then dbeta, dgamma, dx as in cgbn_backward with dz for dy.
  * `dshortcut`, if not NULL, receives dz (the gradient of the shortcut).  dx may be exactly
- * dy, or dshortcut may be exactly dy; dx and dshortcut must differ. */
+ * dy, or dshortcut may be exactly dy; dx and dshortcut must differ (CGBN_ERR_ALIAS). */
 cgbn_status cgbn_backward_relu(const void* dy, const void* y, const void* x,
                                const float* mean, const float* invstd, const float* gamma,
                                void* dx, void* dshortcut, float* dgamma, float* dbeta,

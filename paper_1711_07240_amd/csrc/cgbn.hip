@@ -806,7 +806,7 @@ cgbn_status backward_impl(const void* dy, const void* y, const void* x, const fl
     Plan p;
     CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(y) || !aligned16(dshortcut)) return CGBN_ERR_ALIGN;
-    if (dshortcut && dshortcut == dx) return CGBN_ERR_NULL;
+    if (dshortcut && dshortcut == dx) return CGBN_ERR_ALIAS;
     CGBN_TRY(check_ws(p, workspace, workspace_bytes));
     char* ws = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -901,6 +901,7 @@ const char* cgbn_status_string(cgbn_status status)
     case CGBN_ERR_HIP: return "the HIP runtime refused a launch";
     case CGBN_ERR_TUNING: return "unknown tuning key or value out of range";
     case CGBN_ERR_MOMENTUM: return "momentum outside [0, 1]";
+    case CGBN_ERR_ALIAS: return "two outputs that must differ are the same buffer";
     }
     return "unknown status";
 }

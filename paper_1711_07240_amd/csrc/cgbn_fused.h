@@ -1,10 +1,10 @@
 // Register-resident CGBN for NCHW tensors: each activation value is read from
-// HBM once per direction and kept on chip (VGPRs, plus some LDS for large
-// planes) while the cross-shard reductions complete.
+// HBM once per direction and kept on chip (VGPRs, plus some LDS) while the
+// cross-shard reductions complete.
 //
 // The multi-sweep kernels read x three times in the forward (sum, squared
 // deviations, normalise) and dy, x twice in the backward.  Here a workgroup
-// takes a *unit* -- up to 152 KiB of one channel -- into registers, writes its
+// takes a *unit* -- up to 176 KiB of one channel -- into registers, writes its
 // partial sums to the channel's rows, waits until every unit of the channel has
 // done so, reduces the rows itself (shard by shard, then across shards, in double
 // precision, the same arithmetic as combine_rows and the same in every
@@ -30,7 +30,10 @@
 // images per wavefront, each in LPPC register slots (a template parameter, the
 // smallest instantiated count that holds the plane); a unit is up to 4*P planes
 // of one channel and leaves one row per plane.  Rows are ordered by image, hence
-// shard by shard.
+// shard by shard.  The LDS not taken by unit data stages a channel's rows and
+// shard sums while they are reduced; a channel with few of both (BIG != 0) needs
+// little of that, and its units keep 48 KiB (large planes, BIG == 1) or 44 KiB
+// (small planes, BIG == 2: further whole planes per wavefront) of data in LDS.
 //
 // Scheduling.  The grid is persistent and no larger than what is resident at
 // once; workgroup b takes units b, b + G, b + 2G, ... in channel-major order.
@@ -201,7 +204,7 @@ template <> struct LdsSlot<8> {
         *reinterpret_cast<u32x2*>(ext + ((size_t)j * kThreads + t) * 2) = v;
     }
 };
-template <> struct LdsSlot<4> {      // never used: 4-byte variants keep everything in registers
+template <> struct LdsSlot<4> {      // placeholder: the 4-byte variants keep everything in registers (RL == 0)
     static __device__ __forceinline__ void fill(const char*, const char*, unsigned, uint32_t*, int, int, int) {}
     static __device__ __forceinline__ void read(const uint32_t*, int, int, uint32_t* out) { out[0] = 0u; }
     static __device__ __forceinline__ void write(uint32_t*, int, int, const uint32_t*) {}

@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {L.cgbn_status_string(i) for i in range(10)}
-    assert len(seen) == 10 and "ok" in seen
+    seen = {L.cgbn_status_string(i) for i in range(12)}
+    assert len(seen) == 12 and "ok" in seen and "unknown status" not in seen
     assert L.cgbn_status_string(99) == "unknown status"
 
 

@@ -286,6 +286,39 @@ def test_mean_lo_matters_only_for_offset_data_and_null_is_accepted():
     check_against_oracle(r, ref, "f32", "offset with mean_lo")
 
 
+FEW_GROUPS = [
+    # (shape, workgroups): large planes, one tile per plane -> 8 units per channel
+    ("large-planes-8-units", dict(N=8, C=12, H=96, W=128, K=4, layout="NCHW", dtype="f32"), (8, 9, 13)),
+    # small planes of 1050 floats, 64 images -> 2 units per channel forward, 4 backward
+    ("small-planes-64-images", dict(N=64, C=10, H=25, W=42, K=16, layout="NCHW", dtype="f32"), (4, 5, 7)),
+    ("small-planes-bf16", dict(N=96, C=6, H=25, W=44, K=8, layout="NCHW", dtype="bf16"), (4, 6)),
+]
+
+
+@pytest.mark.parametrize("name,kw,groups", FEW_GROUPS, ids=[c[0] for c in FEW_GROUPS])
+def test_few_workgroups_walk_many_units(name, kw, groups, path):
+    """The single-launch grid is persistent: with few workgroups each one takes several units of several
+    channels in turn (registers, LDS slots and the staging area reused from unit to unit), and a grid that is
+    not a whole number of channels leaves channels straddling two rounds."""
+    if not path:
+        pytest.skip("the multi-sweep kernels have no persistent grid")
+    wl = BASE.scaled(name=name, **kw)
+    d = synth.make_inputs(wl)
+    ref = oracle_all(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype)
+    old = L.cgbn_get_tuning("fused_groups")
+    try:
+        for g in groups:
+            print(f"[case] {name}: {g} workgroups", flush=True)
+            L.cgbn_set_tuning("fused_groups", g)
+            p = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
+            p.forward(); p.backward()
+            torch.cuda.synchronize()
+            assert L.cgbn_get_tuning("last_forward_fused") == 1 and L.cgbn_get_tuning("last_backward_fused") == 1
+            check_against_oracle(p.results(), ref, wl.dtype, f"{name} with {g} workgroups")
+    finally:
+        L.cgbn_set_tuning("fused_groups", old)
+
+
 def test_bounded_wait_gives_up_cleanly(path):
     """Failure handling of the single-launch kernels, forced from the host: with a
     poll limit of zero a wait gives up unless its flag is already set.  The grid

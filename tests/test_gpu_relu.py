@@ -150,7 +150,7 @@ def test_relu_argument_errors():
     with pytest.raises(L.CgbnError) as e:       # dx and dshortcut must differ
         L.cgbn_backward_relu(p.dy, p.y, p.x, p.mean, p.invstd, p.gamma, p.dx, p.dx, p.dgamma, p.dbeta, *p.shape_args,
                              wl.layout, wl.K, wl.dtype, p.mean_lo, p.ws)
-    assert e.value.code == 1
+    assert e.value.code == 11
 
 
 @pytest.mark.parametrize("name", ["cfg1", "cfg3"])

@@ -366,7 +366,8 @@ def main():
         "config": {"workload": f"{wl.name}: N={wl.N} C={wl.C} H={wl.H} W={wl.W} {wl.layout} {wl.dtype} K={wl.K}",
                    "step": "cgbn_forward + cgbn_backward", "algorithmic_bytes": 9 * Sb,
                    "tuning": {k: cgbn.cgbn_get_tuning(k) for k in
-                              ("chunk_bytes", "wave_plane_bytes", "piece_bytes", "map_piece_bytes", "reverse", "nt_store", "fused")},
+                              ("chunk_bytes", "wave_plane_bytes", "piece_bytes", "map_piece_bytes", "reverse", "nt_store", "fused",
+                               "big_lds", "stagger", "stagger_us", "stagger_phases", "one_sweep_stats", "cooperative")},
                    "single_launch": head["single_launch"]},
         "pct_of_peak": head["pct_of_peak"], "fwd_ms": head["fwd_ms"], "bwd_ms": head["bwd_ms"],
         "floor_GBps": head["floor_GBps"],

@@ -234,6 +234,11 @@ const char* cgbn_status_string(cgbn_status status);
  *                      planes) shards use variants of the single-launch kernels that stage few rows and keep
  *                      more unit data in LDS
  *   "fused_groups"     workgroups of that launch (0 = all that are resident at once)
+ *   "stagger"          0/1 (default 1): the single-launch kernels start their channel slots class by class, so
+ *                      that the slots' load, hand-over and write-out phases interleave
+ *   "stagger_us"       microseconds by which the last class starts after the first (0, the default: chosen
+ *                      per launch, none for short launches)
+ *   "stagger_phases"   number of such classes (2..64, default 16)
  *   "spin_limit"       polls before a device-side wait gives up
  * cgbn_get_tuning returns -1 for an unknown key. */
 cgbn_status cgbn_set_tuning(const char* key, long long value);

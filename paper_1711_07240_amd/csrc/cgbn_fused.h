@@ -101,6 +101,7 @@ struct FusedArgs {
     int LPP, IPU;         // small planes: loads per lane and plane, images per unit
     int nt;
     unsigned spin_limit;
+    unsigned stagger_ticks, stagger_phases;   // start-up delay between channel slots (100 MHz ticks; 0 = none)
     unsigned plane_stride; // small planes: bytes between the same channel's planes of consecutive images
 };
 
@@ -417,6 +418,19 @@ __device__ __forceinline__ unsigned fresh(unsigned v)
     return v;
 }
 
+// Optional start-up stagger: the grid's channel slots (the channels in flight at once) start in
+// `stagger_phases` classes, class p delayed by p * stagger_ticks, so that the classes' load,
+// hand-over and write-out phases interleave on the memory system instead of coinciding.
+// Bounded like every other wait.
+__device__ __forceinline__ void stagger_start(const FusedArgs& A)
+{
+    if (A.stagger_ticks == 0u || A.stagger_phases < 2u) return;
+    const unsigned cls = ((unsigned)blockIdx.x / (unsigned)A.U) % A.stagger_phases;
+    if (cls == 0u) return;
+    const unsigned long long t0 = wall_clock64(), wait = (unsigned long long)cls * A.stagger_ticks;
+    for (int i = 0; i < (1 << 16) && wall_clock64() - t0 < wait; ++i) __builtin_amdgcn_s_sleep(16);
+}
+
 // A unit's data is addressed as (uniform base pointer) + (32-bit per-lane byte
 // offset) + (compile-time offset), so that every load and store takes a scalar
 // base, one vector register and an immediate.
@@ -518,6 +532,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
     // for, and the launch needs no initialised workspace (the error word is cleared here instead).
     const bool solo = A.U == 1;
     if (solo && blockIdx.x == 0 && t == 0) A.sync[1] = 0u;
+    stagger_start(A);
 
     for (long long unit = blockIdx.x; unit < A.total_units; unit += gridDim.x) {
         UnitGeom g;
@@ -779,6 +794,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
     __shared__ uint32_t ext[RL > 0 ? 2 * RL * W * kThreads : 1];    // dy slots, then x slots
     const bool solo = A.U == 1;     // the channel's only unit: rows stay in LDS (see the forward kernel)
     if (solo && blockIdx.x == 0 && t == 0) A.sync[1] = 0u;
+    stagger_start(A);
 
     for (long long unit = blockIdx.x; unit < A.total_units; unit += gridDim.x) {
         UnitGeom g;

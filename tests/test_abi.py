@@ -116,6 +116,11 @@ def test_tuning_knobs():
         L.cgbn_set_tuning("no_such_key", 1)
     with pytest.raises(L.CgbnError):
         L.cgbn_set_tuning("reverse", 2)
+    with pytest.raises(L.CgbnError):
+        L.cgbn_set_tuning("stagger_us", -1)
+    with pytest.raises(L.CgbnError):
+        L.cgbn_set_tuning("stagger_phases", 1)
+    assert L.cgbn_get_tuning("stagger") == 1 and L.cgbn_get_tuning("stagger_us") == 0 and L.cgbn_get_tuning("stagger_phases") == 16
     old = L.cgbn_get_tuning("chunk_bytes")
     before = L.cgbn_workspace_bytes(16, 64, 400, 672, "NCHW", "f32", 8)
     try:

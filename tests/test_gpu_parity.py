@@ -308,15 +308,22 @@ def test_few_workgroups_walk_many_units(name, kw, groups, path):
     old = L.cgbn_get_tuning("fused_groups")
     try:
         for g in groups:
-            print(f"[case] {name}: {g} workgroups", flush=True)
-            L.cgbn_set_tuning("fused_groups", g)
-            p = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
-            p.forward(); p.backward()
-            torch.cuda.synchronize()
-            assert L.cgbn_get_tuning("last_forward_fused") == 1 and L.cgbn_get_tuning("last_backward_fused") == 1
-            check_against_oracle(p.results(), ref, wl.dtype, f"{name} with {g} workgroups")
+            seen = []
+            for stagger_us in (0, 3):       # 3: the channel slots start class by class, 3 us apart in all
+                print(f"[case] {name}: {g} workgroups, start-up stagger {stagger_us} us", flush=True)
+                L.cgbn_set_tuning("fused_groups", g)
+                L.cgbn_set_tuning("stagger_us", stagger_us)
+                p = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
+                p.forward(); p.backward()
+                torch.cuda.synchronize()
+                assert L.cgbn_get_tuning("last_forward_fused") == 1 and L.cgbn_get_tuning("last_backward_fused") == 1
+                seen.append(p.results())
+                check_against_oracle(seen[-1], ref, wl.dtype, f"{name} with {g} workgroups")
+            for k in seen[0]:               # when a workgroup starts must not change a bit of the result
+                assert np.array_equal(seen[0][k], seen[1][k]), (g, k)
     finally:
         L.cgbn_set_tuning("fused_groups", old)
+        L.cgbn_set_tuning("stagger_us", 0)
 
 
 def test_bounded_wait_gives_up_cleanly(path):

@@ -286,6 +286,32 @@ def test_mean_lo_matters_only_for_offset_data_and_null_is_accepted():
     check_against_oracle(r, ref, "f32", "offset with mean_lo")
 
 
+LIMITS = [
+    # (name, shape, does the single-launch path take it): the limits of what a workgroup stages in LDS
+    ("512-shards", dict(N=512, C=2, H=4, W=5, K=512, layout="NCHW", dtype="f32"), 1),
+    ("520-shards-too-many", dict(N=520, C=2, H=4, W=5, K=520, layout="NCHW", dtype="f32"), 0),
+    ("2048-rows", dict(N=2048, C=2, H=3, W=4, K=64, layout="NCHW", dtype="f32"), 1),
+    ("2050-rows-too-many", dict(N=2050, C=2, H=3, W=4, K=2, layout="NCHW", dtype="f32"), 0),
+    # small planes: 384 rows / 128 shards is the most the variant with planes in LDS stages
+    ("384-rows-128-shards-lds-planes", dict(N=384, C=2, H=25, W=42, K=128, layout="NCHW", dtype="f32"), 1),
+    ("390-rows-130-shards", dict(N=390, C=2, H=25, W=42, K=130, layout="NCHW", dtype="f32"), 1),
+    # large planes, 4 tiles each in the forward: 96 images = 384 rows (variant with more data in LDS), 97 images = 388 rows
+    ("large-planes-384-rows", dict(N=96, C=1, H=300, W=500, K=48, layout="NCHW", dtype="f32"), 1),
+    # (its backward has 8 tiles per plane: 776 units per channel, more than workgroups fit the device at once)
+    ("large-planes-388-rows", dict(N=97, C=1, H=300, W=500, K=1, layout="NCHW", dtype="f32"), (1, 0)),
+    # channels-last: more partial rows than one combine pass of 64 lanes per shard
+    ("nhwc-one-shard-many-pieces", dict(N=1, C=8, H=700, W=900, K=1, layout="NHWC", dtype="bf16"), 0),
+]
+
+
+@pytest.mark.parametrize("name,kw,fused", LIMITS, ids=[c[0] for c in LIMITS])
+def test_limits_of_the_staging_areas(name, kw, fused, path):
+    p, d, got, ref = run_case(BASE.scaled(name=name, **kw), name)
+    if path:
+        fwd, bwd = fused if isinstance(fused, tuple) else (fused, fused)
+        assert L.cgbn_get_tuning("last_forward_fused") == fwd and L.cgbn_get_tuning("last_backward_fused") == bwd
+
+
 FEW_GROUPS = [
     # (shape, workgroups): large planes, one tile per plane -> 8 units per channel
     ("large-planes-8-units", dict(N=8, C=12, H=96, W=128, K=4, layout="NCHW", dtype="f32"), (8, 9, 13)),

@@ -30,7 +30,9 @@
  *   - Errors: the return code only.  Argument errors are found on the host
  *     before any launch and leave every output untouched.  CGBN_ERR_HIP wraps a
  *     failed launch.  NaN/Inf in the data are not errors; they propagate within
- *     their channel.
+ *     their channel.  Per-row partial sums are floats (cross-row sums doubles), so
+ *     a channel's squared deviations must stay inside float range (|x - mean| up
+ *     to about 1e18) for the stated accuracy.
  *   - Aliasing: y may be exactly x, dx may be exactly dy; any other overlap of
  *     an output with another argument is undefined.
  *   - `mean_lo` (optional, may be NULL everywhere): float[C] holding the part of

@@ -270,6 +270,31 @@ def test_nan_stays_in_its_channel():
     check_against_oracle(got, ref, "f32", "nan-free channels")
 
 
+@pytest.mark.parametrize("layout", ["NCHW", "NHWC"])
+def test_infinity_stays_in_its_channel(layout):
+    """+Inf in one channel: that channel's statistics and outputs are non-finite (Inf - Inf is NaN), nothing finite
+    is invented, and every other channel is untouched."""
+    wl = BASE.scaled(N=4, C=8, H=12, W=20, K=2, layout=layout)
+    d = synth.make_inputs(wl)
+    bad = 5
+    if layout == "NCHW":
+        d["x"][2, bad, 3, 4] = np.inf
+        chan = lambda a, c: a[:, c]
+    else:
+        d["x"][2, 3, 4, bad] = np.inf
+        chan = lambda a, c: a[..., c]
+    p = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
+    p.forward(); p.backward()
+    r = p.results()
+    assert not np.isfinite(r["mean"][bad]) and not np.any(np.isfinite(chan(r["y"], bad)))
+    keep = [c for c in range(wl.C) if c != bad]
+    clean = synth.make_inputs(wl)
+    ref = oracle_all(chan(clean["x"], keep), chan(clean["dy"], keep), clean["gamma"][keep], clean["beta"][keep],
+                     wl.eps, wl.layout, wl.dtype)
+    got = {k: (chan(v, keep) if v.ndim == 4 else v[keep]) for k, v in r.items()}
+    check_against_oracle(got, ref, "f32", "channels without the infinity")
+
+
 def test_mean_lo_matters_only_for_offset_data_and_null_is_accepted():
     wl = synth.WORKLOADS["cfg4b"].scaled(N=4, C=16, H=20, W=21, K=2)
     d = synth.make_inputs(wl)

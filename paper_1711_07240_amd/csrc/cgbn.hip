@@ -135,12 +135,15 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
         f->LPPC = lppc;
         // with few rows and shards to stage, further whole planes per wavefront go to LDS
         int lds_planes = 0;
-        if (g_tune.big_lds && LB >= 8 && N <= kFusedMaxRowsBig && K <= kFusedMaxShardsBigSmall) {
+        if (g_tune.big_lds && N <= kFusedMaxRowsBig && K <= kFusedMaxShardsBigSmall) {
             bool built = false;
 #define CGBN_IS_BUILT(LB_, LPPC_) built = built || (LB == LB_ && lppc == LPPC_);
             CGBN_FUSED_BIG_SMALL(CGBN_IS_BUILT)
 #undef CGBN_IS_BUILT
             if (built) lds_planes = (lds_words_big_small / W) / lppc;
+            // ... if that makes the channel's units fewer (else the variant only costs its extra slot checks)
+            const int regs_only = 4 * (R / lppc), with_lds = 4 * (R / lppc + lds_planes);
+            if ((N + with_lds - 1) / with_lds >= (N + regs_only - 1) / regs_only) lds_planes = 0;
         }
         f->big = lds_planes > 0 ? 2 : 0;
         int per_unit = 4 * (R / lppc + lds_planes);

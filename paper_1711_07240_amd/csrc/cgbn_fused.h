@@ -157,8 +157,9 @@ template <> struct Words<4> {
 // Unit data beyond the registers: slot j of thread t lives at byte (j*256 + t)*LB of `ext`,
 // i.e. a wavefront's part of a slot is a linear image of 64*LB bytes of global memory.  It
 // is filled by global-to-LDS loads, so the data never passes through registers on its way
-// in: one 16-byte load per lane (LB == 16), or two 4-byte loads per lane for the two halves
-// of the wavefront's 512 bytes (LB == 8; there is no 8-byte global-to-LDS load).
+// in: one 16-byte load per lane (LB == 16), two 4-byte loads per lane for the two halves
+// of the wavefront's 512 bytes (LB == 8; there is no 8-byte global-to-LDS load), or one
+// 4-byte load per lane (LB == 4).
 //   lane_src  this lane's own LB bytes in global memory (what a register slot would load)
 //   wave_src  the first byte of the wavefront's part of the slot (uniform)
 //   valid     bytes of that part that belong to the unit (uniform); lanes past it re-read its start
@@ -205,10 +206,18 @@ template <> struct LdsSlot<8> {
         *reinterpret_cast<u32x2*>(ext + ((size_t)j * kThreads + t) * 2) = v;
     }
 };
-template <> struct LdsSlot<4> {      // placeholder: the 4-byte variants keep everything in registers (RL == 0)
-    static __device__ __forceinline__ void fill(const char*, const char*, unsigned, uint32_t*, int, int, int) {}
-    static __device__ __forceinline__ void read(const uint32_t*, int, int, uint32_t* out) { out[0] = 0u; }
-    static __device__ __forceinline__ void write(uint32_t*, int, int, const uint32_t*) {}
+template <> struct LdsSlot<4> {      // one 4-byte global-to-LDS load per lane
+    static __device__ __forceinline__ void fill(const char*, const char* wave_src, unsigned valid, uint32_t* ext, int j, int w,
+                                                int lane)
+    {
+        unsigned l4 = (unsigned)lane * 4u;
+        asm volatile("" : "+v"(l4));       // recomputed per slot (see LdsSlot<8>)
+        __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)(wave_src + (l4 < valid ? l4 : 0u)),
+                                         (void __attribute__((address_space(3)))*)(ext + ((size_t)j * kThreads + (size_t)w * kWave)),
+                                         4, 0, 0);
+    }
+    static __device__ __forceinline__ void read(const uint32_t* ext, int j, int t, uint32_t* out) { out[0] = ext[(size_t)j * kThreads + t]; }
+    static __device__ __forceinline__ void write(uint32_t* ext, int j, int t, const uint32_t* in) { ext[(size_t)j * kThreads + t] = in[0]; }
 };
 
 // the elements packed in one 32-bit register
@@ -509,8 +518,8 @@ struct Slots {
 template <typename T, int LB, int LPPC, int ACT, int BIG>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 {
-    static_assert(BIG == 0 || (BIG == 1 && LPPC == 0 && LB == 16) || (BIG == 2 && LPPC > 0 && LB >= 8),
-                  "BIG 1: large planes with 16-byte loads; BIG 2: small planes with 8- or 16-byte loads");
+    static_assert(BIG == 0 || (BIG == 1 && LPPC == 0 && LB == 16) || (BIG == 2 && LPPC > 0),
+                  "BIG 1: large planes with 16-byte loads; BIG 2: small planes");
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
     constexpr int R = kFusedWords / W;                                       // slots the registers offer
     using SL = Slots<T, LB, LPPC, R>;
@@ -774,8 +783,8 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 template <typename T, int LB, int LPPC, int ACT, int BIG>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
 {
-    static_assert(BIG == 0 || (BIG == 1 && LPPC == 0 && LB == 16) || (BIG == 2 && LPPC > 0 && LB >= 8),
-                  "BIG 1: large planes with 16-byte loads; BIG 2: small planes with 8- or 16-byte loads");
+    static_assert(BIG == 0 || (BIG == 1 && LPPC == 0 && LB == 16) || (BIG == 2 && LPPC > 0),
+                  "BIG 1: large planes with 16-byte loads; BIG 2: small planes");
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
     constexpr int R = kFusedWords / 2 / W;       // slots per tensor the registers offer
     using SL = Slots<T, LB, LPPC, R>;

@@ -15,4 +15,5 @@
 
 // Small planes with few rows and shards to stage (BIG == 2): further whole planes per wavefront in LDS.
 // Only slot counts for which at least one plane fits the LDS share of either direction.
-#define CGBN_FUSED_BIG_SMALL(X) X(8, 4) X(8, 5) X(8, 6) X(8, 8) X(8, 10) X(16, 2) X(16, 3) X(16, 4) X(16, 5)
+#define CGBN_FUSED_BIG_SMALL(X)                                                               \
+    X(4, 8) X(4, 10) X(4, 12) X(4, 16) X(8, 4) X(8, 5) X(8, 6) X(8, 8) X(8, 10) X(16, 2) X(16, 3) X(16, 4) X(16, 5)

@@ -91,6 +91,9 @@ SMALL = [
     ("nchw-f32-plane1050-n32", dict(N=32, C=6, H=25, W=42, K=8, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane600-n48", dict(N=48, C=3, H=20, W=30, K=4, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane1100-n56", dict(N=56, C=4, H=25, W=44, K=7, layout="NCHW", dtype="bf16")),
+    # ... with 4-byte accesses (bf16 25x42 planes are 2100 bytes; fp32 13x21 planes 1092)
+    ("nchw-bf16-plane1050-n64", dict(N=64, C=3, H=25, W=42, K=8, layout="NCHW", dtype="bf16")),
+    ("nchw-f32-plane273-n80", dict(N=80, C=4, H=13, W=21, K=8, layout="NCHW", dtype="f32")),
     # large planes: tiles that spill past the registers into LDS slots, ragged last tile
     ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),

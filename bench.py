@@ -375,7 +375,6 @@ def main():
         "sweeps": sweeps, "fixed_statistics_mode": frozen, "relu_variants": relu, "roofline": roofline, "cpu_baseline": cpu, "other_workloads": others,
         "device": torch.cuda.get_device_name(0), "hip": torch.version.hip,
         "compute_units": torch.cuda.get_device_properties(0).multi_processor_count,
-        "clock_MHz": (getattr(torch.cuda.get_device_properties(0), "clock_rate", 0) or 0) / 1e3,
         "hbm_GiB": torch.cuda.get_device_properties(0).total_memory / 2 ** 30,
     }
     print(json.dumps(out), flush=True)

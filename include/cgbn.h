@@ -248,6 +248,23 @@ cgbn_status cgbn_set_tuning(const char* key, long long value);
  * cgbn_forward / cgbn_backward took the single-launch path) */
 long long cgbn_get_tuning(const char* key);
 
+/* One number of the launch plan the library would use for this problem under the current
+ * knobs; host-only, launches nothing, -1 for invalid arguments or an unknown key.  For tests
+ * of the host-side planning (every kernel trusts these numbers for its indexing).
+ * Multi-sweep kernels: "grid" (workgroups of a reduction sweep), "gridm" (of a channels-last
+ * elementwise sweep), "rows" / "rps" (row partials per channel / per shard), "G" (lanes adding
+ * one shard's rows), "part_bytes" / "shard_bytes" (workspace bytes of one array of row partials /
+ * of shard sums); NCHW: "wave_mode" (one wavefront per plane), "L" / "sp" (chunk elements, chunks
+ * per plane); NHWC: "vec" (elements per access), "cv" (accesses per pixel), "TW" / "ctiles"
+ * (accesses per pixel handled by one workgroup, workgroups per pixel), "rpp" (pixels per pass),
+ * "PL" / "pps" (pixels per piece, pieces per shard; reductions), "PLm" / "ppsm" (elementwise).
+ * Single-launch kernels, prefix "fwd_" or "bwd_": "ok" (the shape qualifies), "LB" (bytes per
+ * access), "LPPC" (register slots per small plane; 0: large planes), "LPP" (slots a plane fills),
+ * "IPU" (images per unit), "U" (units per channel), "tp" / "TL" (tiles per large plane, tile
+ * elements), "rows", "rps", "G", "big" (0, or which LDS variant), "total_units". */
+long long cgbn_plan_get(int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype, int K,
+                        const char* key);
+
 /* A plain device-to-device copy of `bytes` bytes (a multiple of 16, both
  * pointers 16-byte aligned) by a kernel of this library: it reads and writes a
  * known number of bytes, which is what hardware traffic counters are calibrated

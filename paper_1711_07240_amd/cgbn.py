@@ -56,6 +56,7 @@ SIGNATURES = {
     "cgbn_status_string": (ctypes.c_char_p, [_c_int]),
     "cgbn_set_tuning": (_c_int, [ctypes.c_char_p, _c_ll]),
     "cgbn_get_tuning": (_c_ll, [ctypes.c_char_p]),
+    "cgbn_plan_get": (_c_ll, [_c_int] * 4 + [_c_int, _c_int, _c_int, ctypes.c_char_p]),
 }
 
 _lib = None
@@ -245,3 +246,7 @@ def cgbn_set_tuning(key: str, value: int) -> None:
 
 def cgbn_get_tuning(key: str) -> int:
     return int(lib().cgbn_get_tuning(key.encode()))
+
+
+def cgbn_plan_get(N, C, H, W, layout, dtype, K, key: str) -> int:
+    return int(lib().cgbn_plan_get(N, C, H, W, _enum(LAYOUTS, layout), _enum(DTYPES, dtype), K, key.encode()))

@@ -1003,6 +1003,51 @@ cgbn_status cgbn_calibration_copy(const void* src, void* dst, size_t bytes, void
     return launched();
 }
 
+long long cgbn_plan_get(int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype, int K, const char* key)
+{
+    Plan p;
+    if (!key || make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return -1;
+    const bool bwd = !std::strncmp(key, "bwd_", 4);
+    if (bwd || !std::strncmp(key, "fwd_", 4)) {
+        const FusedPlan& f = bwd ? p.fb : p.ff;
+        const char* k = key + 4;
+        if (!std::strcmp(k, "ok")) return f.ok;
+        if (!std::strcmp(k, "LB")) return f.LB;
+        if (!std::strcmp(k, "LPPC")) return f.LPPC;
+        if (!std::strcmp(k, "LPP")) return f.LPP;
+        if (!std::strcmp(k, "IPU")) return f.IPU;
+        if (!std::strcmp(k, "U")) return f.U;
+        if (!std::strcmp(k, "tp")) return f.tp;
+        if (!std::strcmp(k, "TL")) return f.TL;
+        if (!std::strcmp(k, "rows")) return f.rows;
+        if (!std::strcmp(k, "rps")) return f.rps;
+        if (!std::strcmp(k, "G")) return f.G;
+        if (!std::strcmp(k, "big")) return f.big;
+        if (!std::strcmp(k, "total_units")) return f.total_units;
+        return -1;
+    }
+    if (!std::strcmp(key, "wave_mode")) return p.wave_mode;
+    if (!std::strcmp(key, "L")) return p.L;
+    if (!std::strcmp(key, "sp")) return p.sp;
+    if (!std::strcmp(key, "vec")) return p.vec;
+    if (!std::strcmp(key, "cv")) return p.cv;
+    if (!std::strcmp(key, "TW")) return p.TW;
+    if (!std::strcmp(key, "ctiles")) return p.ctiles;
+    if (!std::strcmp(key, "rpp")) return p.rpp;
+    if (!std::strcmp(key, "PL")) return p.PL;
+    if (!std::strcmp(key, "pps")) return p.pps;
+    if (!std::strcmp(key, "PLm")) return p.PLm;
+    if (!std::strcmp(key, "ppsm")) return p.ppsm;
+    if (!std::strcmp(key, "rows")) return p.rows;
+    if (!std::strcmp(key, "rps")) return p.rps;
+    if (!std::strcmp(key, "G")) return p.G;
+    if (!std::strcmp(key, "grid")) return p.grid;
+    if (!std::strcmp(key, "gridm")) return p.gridm;
+    if (!std::strcmp(key, "part_bytes")) return (long long)(p.off_part1 - p.off_part0);
+    if (!std::strcmp(key, "shard_bytes")) return (long long)(p.off_sh1 - p.off_sh0);
+    return -1;
+}
+
 long long cgbn_get_tuning(const char* key)
 {
     if (key && !std::strcmp(key, "last_forward_fused")) return g_last_forward_fused;

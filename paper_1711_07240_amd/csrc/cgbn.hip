@@ -153,6 +153,16 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
         if ((long long)f->IPU * C * HW * eb > 0x7fffffffLL) return;
         f->rows = N;
         f->rps = ips;
+    } else if (LB >= 8 && HW <= (long long)(R + lds_words / W) * kWave * E) {
+        // a plane a few slots too long for a wavefront's registers: still one plane per wavefront, the last
+        // slots in LDS (four planes per unit instead of the one a "large plane" unit would hold)
+        f->LPP = (int)((HW + (long long)kWave * E - 1) / ((long long)kWave * E));
+        f->LPPC = R + lds_words / W;
+        f->U = (N + 3) / 4;
+        f->IPU = (N + f->U - 1) / f->U;
+        if ((long long)f->IPU * C * HW * eb > 0x7fffffffLL) return;
+        f->rows = N;
+        f->rps = ips;
     } else {
         // large planes: a tile also fills the LDS slots (16-byte loads only); with few rows and shards to
         // stage, the variant with more LDS slots is taken

@@ -29,8 +29,9 @@
 // are taken whole, one plane per wavefront at a time, P planes of consecutive
 // images per wavefront, each in LPPC register slots (a template parameter, the
 // smallest instantiated count that holds the plane); a unit is up to 4*P planes
-// of one channel and leaves one row per plane.  Rows are ordered by image, hence
-// shard by shard.  The LDS not taken by unit data stages a channel's rows and
+// of one channel and leaves one row per plane.  A plane a few slots too long for
+// that share (LPPC greater than the register slots) is still taken by one wavefront,
+// its last slots in LDS.  Rows are ordered by image, hence shard by shard.  The LDS not taken by unit data stages a channel's rows and
 // shard sums while they are reduced; a channel with few of both (BIG != 0) needs
 // little of that, and its units keep 48 KiB (large planes, BIG == 1) or 44 KiB
 // (small planes, BIG == 2: further whole planes per wavefront) of data in LDS.
@@ -524,9 +525,13 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
     constexpr int R = kFusedWords / W;                                       // slots the registers offer
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
-    constexpr int RS = SMALL ? (R / LPPC) * LPPC : R;                        // register slots in use (whole planes)
-    // slots held in LDS: large planes with 16-byte loads; small planes (BIG == 2): whole planes
-    constexpr int RL = SMALL ? (BIG == 2 ? (kFusedLdsWordsBigSmall / W / LPPC) * LPPC : 0)
+    // A plane a few slots too long for a wavefront's registers (LPPC > R): one plane per wavefront, its last slots in LDS
+    constexpr bool SPILL = SMALL && LPPC > R;
+    static_assert(!SPILL || (BIG == 0 && (LPPC - R) * W <= kFusedLdsWords), "the spilled slots must fit the ordinary LDS share");
+    constexpr int RS = SPILL ? R : SMALL ? (R / LPPC) * LPPC : R;            // register slots in use (whole planes)
+    // slots held in LDS: large planes with 16-byte loads; small planes: whole planes (BIG == 2) or a plane's last slots
+    constexpr int RL = SPILL ? LPPC - R
+                     : SMALL ? (BIG == 2 ? (kFusedLdsWordsBigSmall / W / LPPC) * LPPC : 0)
                              : (LB == 16 ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / W : 0);
     constexpr int RT = RS + RL;
     __shared__ ReduceLdsT<BIG> lds;
@@ -789,8 +794,11 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
     constexpr int R = kFusedWords / 2 / W;       // slots per tensor the registers offer
     using SL = Slots<T, LB, LPPC, R>;
     constexpr bool SMALL = SL::SMALL;
-    constexpr int RS = SMALL ? (R / LPPC) * LPPC : R;                        // register slots in use (whole planes)
-    constexpr int RL = SMALL ? (BIG == 2 ? (kFusedLdsWordsBigSmall / 2 / W / LPPC) * LPPC : 0)
+    constexpr bool SPILL = SMALL && LPPC > R;                                // see the forward kernel
+    static_assert(!SPILL || (BIG == 0 && (LPPC - R) * W <= kFusedLdsWords / 2), "the spilled slots must fit the ordinary LDS share");
+    constexpr int RS = SPILL ? R : SMALL ? (R / LPPC) * LPPC : R;            // register slots in use (whole planes)
+    constexpr int RL = SPILL ? LPPC - R
+                     : SMALL ? (BIG == 2 ? (kFusedLdsWordsBigSmall / 2 / W / LPPC) * LPPC : 0)
                              : (LB == 16 ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / 2 / W : 0);   // ... and in LDS
     constexpr int RT = RS + RL;
     __shared__ ReduceLdsT<BIG> lds;

@@ -94,6 +94,14 @@ SMALL = [
     # ... with 4-byte accesses (bf16 25x42 planes are 2100 bytes; fp32 13x21 planes 1092)
     ("nchw-bf16-plane1050-n64", dict(N=64, C=3, H=25, W=42, K=8, layout="NCHW", dtype="bf16")),
     ("nchw-f32-plane273-n80", dict(N=80, C=4, H=13, W=21, K=8, layout="NCHW", dtype="f32")),
+    # planes a few slots too long for a wavefront's registers: one plane per wavefront, the last slots in LDS
+    # (50x84 floats: backward; 100x168 bf16 and 90x100 floats: forward; 22x191 and 2x4099 floats: 8-byte accesses)
+    ("nchw-f32-plane4200-spill-bwd", dict(N=10, C=3, H=50, W=84, K=5, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane16800-spill-fwd", dict(N=6, C=2, H=100, W=168, K=3, layout="NCHW", dtype="bf16")),
+    ("nchw-f32-plane9000-spill-fwd", dict(N=5, C=2, H=90, W=100, K=1, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane4202-spill-bwd-8byte", dict(N=6, C=3, H=22, W=191, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane8198-spill-fwd-8byte", dict(N=4, C=2, H=2, W=4099, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane9200-spill-bwd", dict(N=8, C=2, H=92, W=100, K=4, layout="NCHW", dtype="bf16")),
     # large planes: tiles that spill past the registers into LDS slots, ragged last tile
     ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),

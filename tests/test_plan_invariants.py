@@ -91,8 +91,12 @@ def _check_fused(shape, direction):
     if LPPC > 0:                                     # small planes, whole, LPPC slots each
         assert big in (0, 2)
         LPP = g("LPP")
-        assert LPP == _ceil(HW, WAVE * E) and LPP <= LPPC <= R
-        per_wave = R // LPPC + ((ldsw // Wd) // LPPC if big == 2 else 0)
+        assert LPP == _ceil(HW, WAVE * E) and LPP <= LPPC
+        if LPPC > R:                                 # one plane per wavefront, its last slots in LDS
+            assert big == 0 and LPPC == R + ldsw // Wd and LB >= 8
+            per_wave = 1
+        else:
+            per_wave = R // LPPC + ((ldsw // Wd) // LPPC if big == 2 else 0)
         IPU = g("IPU")
         assert 1 <= IPU <= 4 * per_wave, "a unit must fit the registers and LDS planes of its workgroup"
         assert U * IPU >= N and (U - 1) * IPU < N

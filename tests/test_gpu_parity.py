@@ -165,6 +165,21 @@ def test_value_distributions_small(kind):
         assert np.all(got["dgamma"] == 0.0)
 
 
+@pytest.mark.parametrize("layout", ["NCHW", "NHWC"])
+@pytest.mark.parametrize("scale", [1e-12, 1e12, 1e17])
+def test_extreme_scales(scale, layout):
+    """Activations of scale 1e-12 (variance far below eps), 1e12 and 1e17 (squared deviations near the top of float
+    range, the limit the header states): the relative tolerances hold at every scale."""
+    wl = BASE.scaled(N=6, C=8, H=33, W=47, K=3, layout=layout)
+    d = synth.make_inputs(wl)
+    x = (d["x"].astype(np.float64) * scale).astype(np.float32)
+    p = Problem(x, d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
+    p.forward(); p.backward()
+    ref = oracle_all(x, d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype)
+    rep = check_against_oracle(p.results(), ref, wl.dtype, f"scale {scale:g}")
+    print(f"[ok] scale {scale:g} {layout}: {rep}", flush=True)
+
+
 def test_hand_examples_on_gpu():
     # the two hand-worked examples of tests/golden, through the HIP path
     from conftest import load_golden

@@ -59,7 +59,10 @@
 extern "C" {
 #endif
 
-typedef enum cgbn_status {
+/* Status, layout and dtype travel as plain ints (any value a caller passes is representable; values outside
+ * the lists below are answered with CGBN_ERR_ENUM, or "unknown status"). */
+typedef int cgbn_status;
+enum {
     CGBN_OK = 0,
     CGBN_ERR_NULL = 1,       /* a required pointer is NULL */
     CGBN_ERR_SHAPE = 2,      /* a dimension is < 1 or the tensor is too large to index */
@@ -72,10 +75,12 @@ typedef enum cgbn_status {
     CGBN_ERR_TUNING = 9,     /* unknown tuning key or value out of range */
     CGBN_ERR_MOMENTUM = 10,  /* momentum outside [0, 1] */
     CGBN_ERR_ALIAS = 11      /* two outputs that must differ are the same buffer */
-} cgbn_status;
+};
 
-typedef enum cgbn_layout { CGBN_NCHW = 0, CGBN_NHWC = 1 } cgbn_layout;
-typedef enum cgbn_dtype { CGBN_F32 = 0, CGBN_BF16 = 1 } cgbn_dtype; /* of x, y, dy, dx */
+typedef int cgbn_layout;
+enum { CGBN_NCHW = 0, CGBN_NHWC = 1 };
+typedef int cgbn_dtype;      /* of x, y, dy, dx */
+enum { CGBN_F32 = 0, CGBN_BF16 = 1 };
 
 /* Bytes of workspace any entry point below needs for this problem (a multiple
  * of 256; the workspace itself must be 256-byte aligned).  Returns 0 if the

@@ -35,6 +35,8 @@ CGBN_FUSED_COMMON(CGBN_DECL_B)
 CGBN_FUSED_BACKWARD_ONLY(CGBN_DECL_B)
 CGBN_DECL_FX(16, 0, 1)
 CGBN_DECL_BX(16, 0, 1)
+CGBN_DECL_FX(16, -2, 1)
+CGBN_DECL_BX(16, -2, 1)
 #define CGBN_DECL_F2(LB_, LPPC_) CGBN_DECL_FX(LB_, LPPC_, 2)
 #define CGBN_DECL_B2(LB_, LPPC_) CGBN_DECL_BX(LB_, LPPC_, 2)
 CGBN_FUSED_BIG_SMALL(CGBN_DECL_F2)
@@ -182,6 +184,15 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
             f->U = (int)(N * tp);
             f->rows = f->U;
             f->rps = (int)(ips * tp);
+            // a plane of at most half the slots: the same channel's planes of two consecutive images per unit
+            const long long unit_slots = R + (LB == 16 ? lw / W : 0);
+            const long long plane_slots = (HW * eb + (long long)kThreads * LB - 1) / ((long long)kThreads * LB);
+            if (LB == 16 && tp == 1 && N >= 2 && 2 * plane_slots <= unit_slots && (long long)C * HW * eb <= 0xffffffffLL) {
+                f->LPPC = -2;
+                f->U = (N + 1) / 2;
+                f->rows = N;
+                f->rps = ips;
+            }
             break;
         }
     }
@@ -536,6 +547,10 @@ cgbn_status launch_fused_t(const FusedPlan& f, FusedArgs& A, int sync_words, hip
     if (f.big && f.LB == 16 && f.LPPC == 0) {
         if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, 0, ACT, 1>, f, A, sync_words, st, taken, moved_bytes);
         else return launch_fused_kernel(nchw_fused_backward<T, 16, 0, ACT, 1>, f, A, sync_words, st, taken, moved_bytes);
+    }
+    if (f.big && f.LB == 16 && f.LPPC == -2) {
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, -2, ACT, 1>, f, A, sync_words, st, taken, moved_bytes);
+        else return launch_fused_kernel(nchw_fused_backward<T, 16, -2, ACT, 1>, f, A, sync_words, st, taken, moved_bytes);
     }
 #define CGBN_FUSED_CASE2(LB_, LPPC_)                                                                         \
     if (f.big == 2 && f.LB == LB_ && f.LPPC == LPPC_) {                                                      \

@@ -31,7 +31,9 @@
 // smallest instantiated count that holds the plane); a unit is up to 4*P planes
 // of one channel and leaves one row per plane.  A plane a few slots too long for
 // that share (LPPC greater than the register slots) is still taken by one wavefront,
-// its last slots in LDS.  Rows are ordered by image, hence shard by shard.  The LDS not taken by unit data stages a channel's rows and
+// its last slots in LDS.  A plane too long for that but at most half a tile shares
+// its workgroup with the same channel's plane of the next image (LPPC == -2), each
+// with its own row.  Rows are ordered by image, hence shard by shard.  The LDS not taken by unit data stages a channel's rows and
 // shard sums while they are reduced; a channel with few of both (BIG != 0) needs
 // little of that, and its units keep 48 KiB (large planes, BIG == 1) or 44 KiB
 // (small planes, BIG == 2: further whole planes per wavefront) of data in LDS.
@@ -451,19 +453,24 @@ struct UnitGeom {
     int c, u;
 };
 
-// LPPC == 0: large planes.  LPPC > 0: small planes, LPPC register slots per plane.
-template <typename T, int LB, int LPPC, int R>
+// LPPC == 0: large planes cut into tiles.  LPPC > 0: small planes, one per wavefront at a time, LPPC slots per
+// plane.  LPPC < 0: planes of up to half a tile, -LPPC of them (consecutive images) per workgroup, each in SPW
+// workgroup-wide slots.
+template <typename T, int LB, int LPPC, int R, int SPW = 1>
 struct Slots {
     static constexpr bool SMALL = LPPC > 0;
+    static constexpr bool WGP = LPPC < 0;            // several whole planes per workgroup
+    static constexpr int PPU = WGP ? -LPPC : 1;      // ... that many
     static constexpr int SPP = SMALL ? LPPC : 1;     // slots per plane
 
     static __device__ __forceinline__ void geometry(const FusedArgs& A, long long unit, UnitGeom& g)
     {
         g.c = (int)(unit / A.U);
         g.u = (int)(unit - (long long)g.c * A.U);
-        if (SMALL) {
-            g.n0 = g.u * A.IPU;
-            g.n1 = min(A.N, g.n0 + A.IPU);
+        if (SMALL || WGP) {
+            const int ipu = WGP ? PPU : A.IPU;
+            g.n0 = g.u * ipu;
+            g.n1 = min(A.N, g.n0 + ipu);
             g.base = (((long long)g.n0 * A.C + g.c) * A.HW) * (long long)sizeof(T);
             g.len = A.HW * (int)sizeof(T);
         } else {
@@ -484,20 +491,27 @@ struct Slots {
     static __device__ __forceinline__ bool in_use(const FusedArgs& A, const UnitGeom& g, int s, int w)
     {
         if (SMALL) return image(g, s, w) < g.n1 && (s % SPP) < A.LPP;
+        if (WGP) return g.n0 + s / SPW < g.n1 && (s % SPW) * (kThreads * LB) < g.len;
         return s * (kThreads * LB) < g.len;
     }
     // uniform byte offset of the slot's plane from the unit's base
     static __device__ __forceinline__ size_t plane_base(const FusedArgs& A, int s, int w)
     {
         if (SMALL) return (size_t)(w + 4 * (s / SPP)) * A.plane_stride;
+        if (WGP) return (size_t)(s / SPW) * A.plane_stride;
         return 0;
     }
-    static constexpr int slot_offset(int s) { return SMALL ? (s % SPP) * (kWave * LB) : s * (kThreads * LB); }
+    static constexpr int slot_offset(int s)
+    {
+        return SMALL ? (s % SPP) * (kWave * LB) : WGP ? (s % SPW) * (kThreads * LB) : s * (kThreads * LB);
+    }
     static __device__ __forceinline__ bool lane_ok(const UnitGeom& g, int s, unsigned loff)
     {
         return (unsigned)slot_offset(s) + loff < (unsigned)g.len;
     }
     static constexpr bool ends_plane(int s) { return SMALL && (s % SPP) == SPP - 1; }
+    // workgroup-wide planes: slot s is the last of plane s / SPW (one row per plane, summed across the wavefronts)
+    static constexpr bool ends_wg_plane(int s) { return WGP && (s % SPW) == SPW - 1; }
     // For LDS slots: byte offset (from the unit's base) of the part of slot s that wavefront w fills, and how
     // many bytes of that part belong to the unit (both uniform)
     static __device__ __forceinline__ size_t wave_base(const FusedArgs& A, int s, int w)
@@ -519,12 +533,12 @@ struct Slots {
 template <typename T, int LB, int LPPC, int ACT, int BIG>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 {
-    static_assert(BIG == 0 || (BIG == 1 && LPPC == 0 && LB == 16) || (BIG == 2 && LPPC > 0),
+    static_assert(BIG == 0 || (BIG == 1 && LPPC <= 0 && LB == 16) || (BIG == 2 && LPPC > 0),
                   "BIG 1: large planes with 16-byte loads; BIG 2: small planes");
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
     constexpr int R = kFusedWords / W;                                       // slots the registers offer
-    using SL = Slots<T, LB, LPPC, R>;
-    constexpr bool SMALL = SL::SMALL;
+    constexpr bool SMALL = LPPC > 0, WGP = LPPC < 0;
+    static_assert(!WGP || LB == 16, "several planes per workgroup: 16-byte loads only");
     // A plane a few slots too long for a wavefront's registers (LPPC > R): one plane per wavefront, its last slots in LDS
     constexpr bool SPILL = SMALL && LPPC > R;
     static_assert(!SPILL || (BIG == 0 && (LPPC - R) * W <= kFusedLdsWords), "the spilled slots must fit the ordinary LDS share");
@@ -534,8 +548,10 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                      : SMALL ? (BIG == 2 ? (kFusedLdsWordsBigSmall / W / LPPC) * LPPC : 0)
                              : (LB == 16 ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / W : 0);
     constexpr int RT = RS + RL;
+    using SL = Slots<T, LB, LPPC, R, WGP ? RT / (WGP ? -LPPC : 1) : 1>;
+    constexpr int SPW = WGP ? RT / SL::PPU : 1;
     __shared__ ReduceLdsT<BIG> lds;
-    __shared__ float s_red[4];
+    __shared__ float s_red[4 * SL::PPU];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
     const T* x = static_cast<const T*>(A.x);
     const char* xb = static_cast<const char*>(A.x);
@@ -606,8 +622,20 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                     }
                     acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
                 }
+                if (SL::ends_wg_plane(s)) {                 // a workgroup-wide plane is complete: its row
+                    const int pl = s / SPW, n = g.n0 + pl;
+                    float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+                    if (lane == 0) s_red[4 * pl + w] = tot;
+                    __syncthreads();
+                    if (t == 0 && n < g.n1) {
+                        const float tot4 = (s_red[4 * pl] + s_red[4 * pl + 1]) + (s_red[4 * pl + 2] + s_red[4 * pl + 3]);
+                        if (solo) lds.rows[0][n] = tot4;
+                        else publish_row(&A.part0[(size_t)c * A.rows + n], tot4);
+                    }
+                    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
+                }
             }
-            if (!SMALL) {
+            if (!SMALL && !WGP) {
                 float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
                 if (lane == 0) s_red[w] = tot;
                 __syncthreads();
@@ -677,8 +705,20 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                     }
                     acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
                 }
+                if (SL::ends_wg_plane(s)) {
+                    const int pl = s / SPW, n = g.n0 + pl;
+                    float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+                    if (lane == 0) s_red[4 * pl + w] = tot;
+                    __syncthreads();
+                    if (t == 0 && n < g.n1) {
+                        const float tot4 = (s_red[4 * pl] + s_red[4 * pl + 1]) + (s_red[4 * pl + 2] + s_red[4 * pl + 3]);
+                        if (solo) lds.rows[0][n] = tot4;
+                        else publish_row(&A.part1[(size_t)c * A.rows + n], tot4);
+                    }
+                    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
+                }
             }
-            if (!SMALL) {
+            if (!SMALL && !WGP) {
                 float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
                 if (lane == 0) s_red[w] = tot;
                 __syncthreads();
@@ -788,12 +828,12 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
 template <typename T, int LB, int LPPC, int ACT, int BIG>
 __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
 {
-    static_assert(BIG == 0 || (BIG == 1 && LPPC == 0 && LB == 16) || (BIG == 2 && LPPC > 0),
+    static_assert(BIG == 0 || (BIG == 1 && LPPC <= 0 && LB == 16) || (BIG == 2 && LPPC > 0),
                   "BIG 1: large planes with 16-byte loads; BIG 2: small planes");
     constexpr int W = LB / 4, EPW = Packed<T>::EPW;
     constexpr int R = kFusedWords / 2 / W;       // slots per tensor the registers offer
-    using SL = Slots<T, LB, LPPC, R>;
-    constexpr bool SMALL = SL::SMALL;
+    constexpr bool SMALL = LPPC > 0, WGP = LPPC < 0;
+    static_assert(!WGP || LB == 16, "several planes per workgroup: 16-byte loads only");
     constexpr bool SPILL = SMALL && LPPC > R;                                // see the forward kernel
     static_assert(!SPILL || (BIG == 0 && (LPPC - R) * W <= kFusedLdsWords / 2), "the spilled slots must fit the ordinary LDS share");
     constexpr int RS = SPILL ? R : SMALL ? (R / LPPC) * LPPC : R;            // register slots in use (whole planes)
@@ -801,8 +841,10 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                      : SMALL ? (BIG == 2 ? (kFusedLdsWordsBigSmall / 2 / W / LPPC) * LPPC : 0)
                              : (LB == 16 ? (BIG ? kFusedLdsWordsBig : kFusedLdsWords) / 2 / W : 0);   // ... and in LDS
     constexpr int RT = RS + RL;
+    using SL = Slots<T, LB, LPPC, R, WGP ? RT / (WGP ? -LPPC : 1) : 1>;
+    constexpr int SPW = WGP ? RT / SL::PPU : 1;
     __shared__ ReduceLdsT<BIG> lds;
-    __shared__ float s_red[8];
+    __shared__ float s_red[8 * SL::PPU];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
     const char* xb = static_cast<const char*>(A.x);
     const char* gb = static_cast<const char*>(A.dy);
@@ -936,8 +978,26 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
                     }
                     a[0] = a[1] = b[0] = b[1] = 0.f;
                 }
+                if (SL::ends_wg_plane(s)) {                 // a workgroup-wide plane is complete: its rows
+                    const int pl = s / SPW, n = g.n0 + pl;
+                    float ta = wave_sum(a[0] + a[1]), tb = wave_sum(b[0] + b[1]);
+                    if (lane == 0) { s_red[8 * pl + w] = ta; s_red[8 * pl + 4 + w] = tb; }
+                    __syncthreads();
+                    if (t == 0 && n < g.n1) {
+                        const float ta4 = (s_red[8 * pl] + s_red[8 * pl + 1]) + (s_red[8 * pl + 2] + s_red[8 * pl + 3]);
+                        const float tb4 = (s_red[8 * pl + 4] + s_red[8 * pl + 5]) + (s_red[8 * pl + 6] + s_red[8 * pl + 7]);
+                        if (solo) {
+                            lds.rows[0][n] = ta4;
+                            lds.rows[1][n] = tb4;
+                        } else {
+                            publish_row(&A.part0[(size_t)c * A.rows + n], ta4);
+                            publish_row(&A.part1[(size_t)c * A.rows + n], tb4);
+                        }
+                    }
+                    a[0] = a[1] = b[0] = b[1] = 0.f;
+                }
             }
-            if (!SMALL) {
+            if (!SMALL && !WGP) {
                 float ta = wave_sum(a[0] + a[1]), tb = wave_sum(b[0] + b[1]);
                 if (lane == 0) { s_red[w] = ta; s_red[4 + w] = tb; }
                 __syncthreads();

@@ -9,14 +9,16 @@ namespace cgbn {
 #define CGBN_X(LB_, LPPC_) template __global__ void nchw_fused_forward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT, 0>(FusedArgs);
 CGBN_FUSED_COMMON(CGBN_X)
 CGBN_FUSED_FORWARD_ONLY(CGBN_X)
-template __global__ void nchw_fused_forward<CGBN_INST_T, 16, 0, CGBN_INST_ACT, 1>(FusedArgs);      // big-LDS variant
+template __global__ void nchw_fused_forward<CGBN_INST_T, 16, 0, CGBN_INST_ACT, 1>(FusedArgs);      // big-LDS variants
+template __global__ void nchw_fused_forward<CGBN_INST_T, 16, -2, CGBN_INST_ACT, 1>(FusedArgs);
 #define CGBN_X2(LB_, LPPC_) template __global__ void nchw_fused_forward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT, 2>(FusedArgs);
 CGBN_FUSED_BIG_SMALL(CGBN_X2)
 #else
 #define CGBN_X(LB_, LPPC_) template __global__ void nchw_fused_backward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT, 0>(FusedArgs);
 CGBN_FUSED_COMMON(CGBN_X)
 CGBN_FUSED_BACKWARD_ONLY(CGBN_X)
-template __global__ void nchw_fused_backward<CGBN_INST_T, 16, 0, CGBN_INST_ACT, 1>(FusedArgs);     // big-LDS variant
+template __global__ void nchw_fused_backward<CGBN_INST_T, 16, 0, CGBN_INST_ACT, 1>(FusedArgs);     // big-LDS variants
+template __global__ void nchw_fused_backward<CGBN_INST_T, 16, -2, CGBN_INST_ACT, 1>(FusedArgs);
 #define CGBN_X2(LB_, LPPC_) template __global__ void nchw_fused_backward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT, 2>(FusedArgs);
 CGBN_FUSED_BIG_SMALL(CGBN_X2)
 #endif

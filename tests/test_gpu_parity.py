@@ -102,6 +102,11 @@ SMALL = [
     ("nchw-f32-plane4202-spill-bwd-8byte", dict(N=6, C=3, H=22, W=191, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane8198-spill-fwd-8byte", dict(N=4, C=2, H=2, W=4099, K=2, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane9200-spill-bwd", dict(N=8, C=2, H=92, W=100, K=4, layout="NCHW", dtype="bf16")),
+    # planes of at most half a tile: the same channel's planes of two consecutive images share a workgroup
+    # (100x168 floats: forward; 100x168 bf16, above: backward; an odd image count leaves the last unit one plane)
+    ("nchw-f32-plane16800-two-per-group", dict(N=5, C=3, H=100, W=168, K=5, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane12600-two-per-group", dict(N=8, C=2, H=75, W=168, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane30000-two-per-group", dict(N=3, C=2, H=150, W=200, K=1, layout="NCHW", dtype="bf16")),
     # large planes: tiles that spill past the registers into LDS slots, ragged last tile
     ("nchw-f32-plane40000", dict(N=2, C=3, H=200, W=200, K=2, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane77500", dict(N=2, C=2, H=250, W=310, K=1, layout="NCHW", dtype="f32")),
@@ -131,7 +136,8 @@ def test_small_shapes(name, kw):
 
 LARGE_PLANES = [c for c in SMALL if c[0] in ("nchw-f32-plane40000", "nchw-f32-plane77500", "nchw-bf16-plane90000",
                                               "nchw-f32-block-ragged", "nchw-bf16-block", "nchw-f32-plane1050-n32",
-                                              "nchw-f32-plane600-n48", "nchw-bf16-plane1100-n56", "nchw-f32-plane1100")]
+                                              "nchw-f32-plane600-n48", "nchw-bf16-plane1100-n56", "nchw-f32-plane1100",
+                                              "nchw-f32-plane16800-two-per-group", "nchw-bf16-plane30000-two-per-group")]
 
 
 @pytest.mark.parametrize("name,kw", LARGE_PLANES, ids=[s[0] for s in LARGE_PLANES])
@@ -141,7 +147,7 @@ def test_large_planes_without_the_big_lds_variant(name, kw, path):
     (the ones shapes with many rows or shards use)."""
     if path == 0:
         pytest.skip("multi-sweep path: no such variant")
-    assert len(LARGE_PLANES) == 9
+    assert len(LARGE_PLANES) == 11
     L.cgbn_set_tuning("big_lds", 0)
     try:
         run_case(BASE.scaled(name=name, **kw), name + " (ordinary LDS split)")

@@ -38,6 +38,7 @@ CASES = [
     ("nchw-bf16-plane1050", dict(N=8, C=12, H=25, W=42, K=4, layout="NCHW", dtype="bf16")),
     ("nchw-f32-plane1050-n32", dict(N=32, C=6, H=25, W=42, K=8, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane1100-n56", dict(N=56, C=4, H=25, W=44, K=7, layout="NCHW", dtype="bf16")),
+    ("nchw-f32-plane16800-two-per-group", dict(N=5, C=3, H=100, W=168, K=5, layout="NCHW", dtype="f32")),
     ("nchw-f32-plane4200-spill-bwd", dict(N=10, C=3, H=50, W=84, K=5, layout="NCHW", dtype="f32")),
     ("nchw-bf16-plane16800-spill-fwd", dict(N=6, C=2, H=100, W=168, K=3, layout="NCHW", dtype="bf16")),
     ("nchw-f32-plane8198-spill-fwd-8byte", dict(N=4, C=2, H=2, W=4099, K=2, layout="NCHW", dtype="f32")),

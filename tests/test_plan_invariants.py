@@ -25,7 +25,7 @@ def _built():
     out = {}
     for name in ("COMMON", "FORWARD_ONLY", "BACKWARD_ONLY", "BIG_SMALL"):
         m = re.search(r"#define CGBN_FUSED_%s\(X\)(.*)" % name, text)
-        out[name] = {(int(a), int(b)) for a, b in re.findall(r"X\((\d+),\s*(\d+)\)", m.group(1))}
+        out[name] = {(int(a), int(b)) for a, b in re.findall(r"X\((\d+),\s*(-?\d+)\)", m.group(1))}
     return out
 
 
@@ -106,6 +106,15 @@ def _check_fused(shape, direction):
         assert (LB, LPPC) in lists, "no such kernel is built"
         if big == 2:
             assert N <= BIG_ROWS and K <= BIG_SHARDS_SMALL
+    elif LPPC == -2:                                 # two planes of at most half a tile per workgroup
+        assert LB == 16 and big in (0, 1) and g("tp") == 1 and N >= 2
+        spw = (R + ldsw // Wd) // 2
+        assert _ceil(HW * eb, THREADS * LB) <= spw, "each plane must fit half the workgroup's slots"
+        assert U == _ceil(N, 2) and rows == N and g("rps") == ips
+        assert C * HW * eb <= 2 ** 32 - 1
+        if big == 1:
+            assert rows <= BIG_ROWS and K <= BIG_SHARDS_LARGE
+        assert (16, -2) in BUILT["COMMON"]
     else:                                            # large planes cut into equal tiles
         assert LB in (8, 16) and big in (0, 1)
         tp, TL = g("tp"), g("TL")

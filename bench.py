@@ -241,7 +241,7 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="cfg1")
-    ap.add_argument("--others", default="cfg0,cfg2,cfg3,cfg4", help="secondary workloads timed with fewer steps ('' = none)")
+    ap.add_argument("--others", default="cfg0,cfg2,cfg3,cfg4,cfg4b", help="secondary workloads timed with fewer steps ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true",
                     help="also run the library's plain copy kernel over 1 GiB (for counter calibration under rocprofv3)")

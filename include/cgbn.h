@@ -88,13 +88,24 @@ enum { CGBN_F32 = 0, CGBN_BF16 = 1 };
 size_t cgbn_workspace_bytes(int N, int C, int H, int W, cgbn_layout layout,
                             cgbn_dtype dtype, int K);
 
-/* Byte offset, inside a workspace for this problem, of a 32-bit word that is 0
- * after cgbn_forward / cgbn_backward unless a bounded device-side wait gave up
- * (it cannot when the launch is sound; if it does, the statistics of the
- * affected channels are NaN).  Read it after synchronising the stream.
- * Returns (size_t)-1 if the arguments are invalid. */
+/* Byte offset, inside a workspace, of a 32-bit word that is 0 after cgbn_forward /
+ * cgbn_backward unless a bounded device-side wait gave up (it cannot when the launch is
+ * sound; if it does, the statistics of the affected channels are NaN).  The offset is the
+ * same for every problem; (size_t)-1 if the arguments are invalid.  Callers that do not
+ * want to read workspace memory themselves use cgbn_workspace_status. */
 size_t cgbn_workspace_error_offset(int N, int C, int H, int W, cgbn_layout layout,
                                    cgbn_dtype dtype, int K);
+
+/* The first-class way to learn of such a give-up: enqueues on `stream` a one-thread kernel
+ * that sets *gave_up (a DEVICE int owned by the caller) to 1 if the error word of
+ * `workspace` is up, and leaves it untouched otherwise.  Call it after the cgbn_forward /
+ * cgbn_backward (or their ReLU variants) it is to watch, on the same stream and before the
+ * next call that uses the workspace (every such call clears the word when it starts).  Zero
+ * *gave_up once, let any number of layers raise it, and read it when the host next
+ * synchronises anyway (once per training step, say): a non-zero value means that some
+ * statistics of that step are NaN because the device was shared with other kernels in a way
+ * the launch could not cope with (see "Concurrency" above and the "cooperative" knob). */
+cgbn_status cgbn_workspace_status(const void* workspace, int* gave_up, void* stream);
 
 /* Algorithm 1, all steps.  In: x, gamma[C], beta[C], eps.  Out: y (same shape,
  * layout and dtype as x; bf16 rounded to nearest-even), mean[C], invstd[C] =
@@ -220,8 +231,12 @@ cgbn_status cgbn_update_running_stats(const float* mean, const float* mean_lo, c
 /* Static, never NULL. */
 const char* cgbn_status_string(cgbn_status status);
 
-/* Launch-shape knobs for measurement sweeps (process-wide, not thread-safe;
- * change them only between calls and re-query cgbn_workspace_bytes afterwards).
+/* Launch-shape knobs for measurement sweeps.  They are process-wide; reading and writing
+ * them is serialised, and every call of the library works on ONE copy of them taken when it
+ * starts, so calls from several host threads are safe and a call never sees half of a
+ * change.  The workspace size depends on some of them: re-query cgbn_workspace_bytes after
+ * a change (a call whose workspace is too small for the knobs it runs under returns
+ * CGBN_ERR_WORKSPACE before launching anything).
  *   "chunk_bytes"      NCHW: bytes of one plane handled by one workgroup
  *   "wave_plane_bytes" NCHW: planes up to this size are handled by one wavefront
  *   "piece_bytes"      NHWC reductions: bytes of one pixel range handled by one workgroup (0, the default:
@@ -246,7 +261,9 @@ const char* cgbn_status_string(cgbn_status status);
  *   "stagger_us"       microseconds by which the last class starts after the first (0, the default: chosen
  *                      per launch, none for short launches)
  *   "stagger_phases"   number of such classes (2..64, default 16)
- *   "spin_limit"       polls before a device-side wait gives up
+ *   "spin_limit"       polls before a device-side wait gives up (0: at once; for tests of that path)
+ *   "wait_us"          microseconds of wall-clock time before it gives up (default 100000); once one wait
+ *                      of a launch has given up, its later waits do so at once
  * cgbn_get_tuning returns -1 for an unknown key. */
 cgbn_status cgbn_set_tuning(const char* key, long long value);
 /* also readable: "last_forward_fused", "last_backward_fused" (1 if the last

@@ -30,6 +30,7 @@ _c_int, _c_ll, _c_f, _c_sz, _c_p = (ctypes.c_int, ctypes.c_longlong, ctypes.c_fl
 SIGNATURES = {
     "cgbn_workspace_bytes": (_c_sz, [_c_int] * 4 + [_c_int, _c_int, _c_int]),
     "cgbn_workspace_error_offset": (_c_sz, [_c_int] * 4 + [_c_int, _c_int, _c_int]),
+    "cgbn_workspace_status": (_c_int, [_c_p, _c_p, _c_p]),
     "cgbn_forward": (_c_int, [_c_p] + [_c_int] * 4 + [_c_int, _c_int, _c_p, _c_p, _c_f,
                               _c_p, _c_p, _c_p, _c_int, _c_p, _c_p, _c_sz, _c_p]),
     "cgbn_backward": (_c_int, [_c_p] * 8 + [_c_int] * 4 + [_c_int, _c_int, _c_int, _c_p,
@@ -129,6 +130,10 @@ def cgbn_workspace_bytes(N, C, H, W, layout, dtype, K) -> int:
 
 def cgbn_workspace_error_offset(N, C, H, W, layout, dtype, K) -> int:
     return int(lib().cgbn_workspace_error_offset(N, C, H, W, _enum(LAYOUTS, layout), _enum(DTYPES, dtype), K))
+
+
+def cgbn_workspace_status(workspace, gave_up, stream=None) -> None:
+    _check(lib().cgbn_workspace_status(_ptr(workspace), _ptr(gave_up), _stream(stream)), "cgbn_workspace_status")
 
 
 def cgbn_forward(x, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd,

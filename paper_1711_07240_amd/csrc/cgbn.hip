@@ -6,6 +6,7 @@
 #include "cgbn_fused.h"
 #include "cgbn_fused_list.h"
 
+#include <atomic>
 #include <cmath>
 #include <cstring>
 #include <map>
@@ -70,9 +71,19 @@ struct Tuning {
     long long stagger = 1;               // single-launch kernels: start the channel slots class by class (see choose_stagger)
     long long stagger_us = 0;            // ... start-up delay of the last class (0 = chosen per launch)
     long long stagger_phases = 16;       // ... and the number of classes
+    long long wait_us = 100000;          // microseconds after which a device-side wait of the fused kernels gives up
 };
+// The knobs are process-wide; every call works on ONE copy of them taken under the lock when it starts
+// (tuning_now), so a knob changed by another thread in the middle of a call cannot make the plan, the
+// workspace check and the launches of that call disagree.
 Tuning g_tune;
-long long g_last_forward_fused = 0, g_last_backward_fused = 0;   // which path the last call took
+std::mutex g_tune_lock;
+Tuning tuning_now()
+{
+    std::lock_guard<std::mutex> hold(g_tune_lock);
+    return g_tune;
+}
+std::atomic<long long> g_last_forward_fused{0}, g_last_backward_fused{0};   // which path the last call took
 #ifdef CGBN_TRACE
 unsigned long long* g_trace = nullptr;
 #endif
@@ -89,6 +100,7 @@ struct FusedPlan {
 };
 
 struct Plan {
+    Tuning t;             // the knobs this plan was made under (the call's own copy)
     int N, C, H, W, K, layout, dtype;
     int eb, vec;          // bytes per element; elements per 16-byte vector (NHWC: 1 if C is not a multiple)
     int HW, ips;
@@ -110,8 +122,8 @@ struct Plan {
 
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words, int lds_words_big,
-                     int lds_words_big_small, FusedPlan* f)
+void make_fused_plan(const Tuning& T, int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words,
+                     int lds_words_big, int lds_words_big_small, FusedPlan* f)
 {
     std::memset(f, 0, sizeof(*f));
     if (K > kFusedMaxShards) return;
@@ -137,7 +149,7 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
         f->LPPC = lppc;
         // with few rows and shards to stage, further whole planes per wavefront go to LDS
         int lds_planes = 0;
-        if (g_tune.big_lds && N <= kFusedMaxRowsBig && K <= kFusedMaxShardsBigSmall) {
+        if (T.big_lds && N <= kFusedMaxRowsBig && K <= kFusedMaxShardsBigSmall) {
             bool built = false;
 #define CGBN_IS_BUILT(LB_, LPPC_) built = built || (LB == LB_ && lppc == LPPC_);
             CGBN_FUSED_BIG_SMALL(CGBN_IS_BUILT)
@@ -169,7 +181,7 @@ void make_fused_plan(int N, int C, long long HW, int K, int layout, int eb, int 
         // large planes: a tile also fills the LDS slots (16-byte loads only); with few rows and shards to
         // stage, the variant with more LDS slots is taken
         const long long gran = (long long)kThreads * E;
-        for (int big = (LB == 16 && g_tune.big_lds && K <= kFusedMaxShardsBig) ? 1 : 0; big >= 0; --big) {
+        for (int big = (LB == 16 && T.big_lds && K <= kFusedMaxShardsBig) ? 1 : 0; big >= 0; --big) {
             const int lw = big ? lds_words_big : lds_words;
             const long long cap = wave_cap * 4 + (LB == 16 ? (long long)(lw / W) * kThreads * E : 0);
             long long tp = (HW + cap - 1) / cap;
@@ -249,7 +261,7 @@ long long reduce_pieces(long long spix, int K, int ctiles, int rpp, long long ti
     return (PL + quantum - 1) / quantum * quantum;
 }
 
-cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, Plan* p)
+cgbn_status make_plan(const Tuning& T, int N, int C, int H, int W, int layout, int dtype, int K, Plan* p)
 {
     if (N < 1 || C < 1 || H < 1 || W < 1) return CGBN_ERR_SHAPE;
     if (layout != CGBN_NCHW && layout != CGBN_NHWC) return CGBN_ERR_ENUM;
@@ -262,6 +274,7 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     long long S = planes * HW;
     if (S > (1LL << 40)) return CGBN_ERR_SHAPE;
     std::memset(p, 0, sizeof(*p));
+    p->t = T;
     p->N = N; p->C = C; p->H = H; p->W = W; p->K = K; p->layout = layout; p->dtype = dtype;
     p->eb = dtype == CGBN_F32 ? 4 : 2;
     p->HW = (int)HW;
@@ -271,13 +284,13 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     const int full_vec = 16 / p->eb;
     if (layout == CGBN_NCHW) {
         p->vec = full_vec;
-        if (HW * p->eb <= g_tune.wave_plane_bytes) {
+        if (HW * p->eb <= T.wave_plane_bytes) {
             p->wave_mode = 1;
             p->L = (int)HW;
             p->sp = 1;
             p->grid = (planes + 3) / 4;
         } else {
-            long long L = g_tune.chunk_bytes / p->eb;
+            long long L = T.chunk_bytes / p->eb;
             L -= L % (kThreads * full_vec);                    // whole vectors for every thread
             if (L < kThreads * full_vec) L = kThreads * full_vec;
             if (L > HW) L = HW;
@@ -295,8 +308,8 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
         p->rpp = kThreads / p->TW;
         p->spix = (long long)p->ips * HW;
         long long PL;
-        if (g_tune.piece_bytes > 0) {
-            PL = g_tune.piece_bytes / ((long long)C * p->eb);
+        if (T.piece_bytes > 0) {
+            PL = T.piece_bytes / ((long long)C * p->eb);
             PL -= PL % (4 * p->rpp);                           // four pixels per thread and pass
             if (PL < 4 * p->rpp) PL = 4 * p->rpp;
         } else {
@@ -310,7 +323,7 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
         p->rows = (int)(pps * K);
         p->rps = (int)pps;
         p->grid = (long long)p->rows * p->ctiles;
-        long long PLm = g_tune.map_piece_bytes / ((long long)C * p->eb);
+        long long PLm = T.map_piece_bytes / ((long long)C * p->eb);
         PLm -= PLm % (4 * p->rpp);
         if (PLm < 4 * p->rpp) PLm = 4 * p->rpp;
         if (PLm > p->spix) PLm = p->spix;
@@ -325,20 +338,22 @@ cgbn_status make_plan(int N, int C, int H, int W, int layout, int dtype, int K, 
     int G = 1;
     while (G < kWave && G < p->rps) G <<= 1;
     p->G = G;
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, kFusedLdsWordsBigSmall, &p->ff);
-    make_fused_plan(N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, kFusedLdsWordsBigSmall / 2, &p->fb);
+    make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, kFusedLdsWordsBigSmall, &p->ff);
+    make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, kFusedLdsWordsBigSmall / 2, &p->fb);
     int max_rows = p->rows;
     if (p->ff.ok && p->ff.rows > max_rows) max_rows = p->ff.rows;
     if (p->fb.ok && p->fb.rows > max_rows) max_rows = p->fb.rows;
+    // the sync area comes first, so that the error word has the same offset in every workspace
+    size_t sync = align256(((size_t)kSyncHeader + 4 * (size_t)C) * sizeof(unsigned));
     size_t part = align256((size_t)C * max_rows * sizeof(float));
     size_t sh = align256((size_t)K * C * sizeof(double));
-    p->off_part0 = 0;
-    p->off_part1 = part;
-    p->off_sh0 = 2 * part;
-    p->off_sh1 = 2 * part + sh;
-    p->off_mlo = 2 * part + 2 * sh;
-    p->off_sync = p->off_mlo + align256((size_t)C * sizeof(float));
-    p->bytes = p->off_sync + align256(((size_t)kSyncHeader + 4 * (size_t)C) * sizeof(unsigned));
+    p->off_sync = 0;
+    p->off_part0 = sync;
+    p->off_part1 = sync + part;
+    p->off_sh0 = sync + 2 * part;
+    p->off_sh1 = sync + 2 * part + sh;
+    p->off_mlo = sync + 2 * part + 2 * sh;
+    p->bytes = p->off_mlo + align256((size_t)C * sizeof(float));
     return CGBN_OK;
 }
 
@@ -365,7 +380,7 @@ SweepArgs sweep_args(const Plan& p)
     A.spix = p.spix;
     A.pivot_stride = p.layout == CGBN_NCHW ? p.HW : 1;
     A.inv_M = (float)(1.0 / p.M);
-    A.nt = (int)g_tune.nt_store;
+    A.nt = (int)p.t.nt_store;
     return A;
 }
 
@@ -484,45 +499,45 @@ template <typename KernelT> int resident_groups(KernelT kernel)
 // class over about half a round interleaves those phases (measured: forward 3-7 % faster, backward
 // 0-3 %, on tensors of 1-2 GB).  The delay is paid once, so it is only taken for launches of at
 // least 8 rounds.  `moved_bytes`: what the launch reads and writes.
-void choose_stagger(const FusedPlan& f, long long groups, double moved_bytes, FusedArgs& A)
+void choose_stagger(const Tuning& T, const FusedPlan& f, long long groups, double moved_bytes, FusedArgs& A)
 {
     A.stagger_ticks = 0;
     A.stagger_phases = 1;
     const long long slots = groups / f.U, rounds = f.total_units / groups;
-    if (!g_tune.stagger || f.U < 2 || slots < 2) return;
-    double spread_us = (double)g_tune.stagger_us;
+    if (!T.stagger || f.U < 2 || slots < 2) return;
+    double spread_us = (double)T.stagger_us;
     if (spread_us <= 0.0) {
         if (rounds < 8) return;
         const double round_us = moved_bytes / (double)f.total_units * (double)groups / 4.5e6;   // at 4.5 TB/s
         spread_us = 0.45 * round_us;
         if (spread_us > 40.0) spread_us = 40.0;
     }
-    const long long phases = slots < g_tune.stagger_phases ? slots : g_tune.stagger_phases;
+    const long long phases = slots < T.stagger_phases ? slots : T.stagger_phases;
     A.stagger_phases = (unsigned)phases;
     A.stagger_ticks = (unsigned)(spread_us * 100.0 / (double)(phases - 1));     // 100 MHz clock
 }
 
 template <typename KernelT>
-cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st,
-                                bool* taken, double moved_bytes)
+cgbn_status launch_fused_kernel(KernelT kernel, const Tuning& T, const FusedPlan& f, FusedArgs& A, int sync_words,
+                                hipStream_t st, bool* taken, double moved_bytes)
 {
     long long groups = resident_groups(kernel);
-    if (g_tune.fused_groups > 0 && g_tune.fused_groups < groups) groups = g_tune.fused_groups;
+    if (T.fused_groups > 0 && T.fused_groups < groups) groups = T.fused_groups;
     if (groups > f.total_units) groups = f.total_units;
     *taken = false;
     if (groups < 1 || f.U > groups) return CGBN_OK;      // a channel's units must all be resident: other path
     // With few channels in flight, a grid that is not a whole number of channels leaves the
     // units of the straddling channel waiting a full round for their siblings: trim it.
-    if (g_tune.fused_groups == 0 && groups / f.U < 8) groups = groups / f.U * f.U;
+    if (T.fused_groups == 0 && groups / f.U < 8) groups = groups / f.U * f.U;
     *taken = true;
-    choose_stagger(f, groups, moved_bytes, A);
+    choose_stagger(T, f, groups, moved_bytes, A);
     if (f.U > 1) {      // a channel's only unit hands nothing over: no rows or counters to prepare
         long long want = (A.row_words + kThreads - 1) / kThreads;
         unsigned init_groups = (unsigned)(want < 1 ? 1 : (want > 2048 ? 2048 : want));
         hipLaunchKernelGGL(fused_init, dim3(init_groups), dim3(kThreads), 0, st, A.sync, sync_words,
                            reinterpret_cast<unsigned*>(A.part0), A.row_words);
     }
-    if (f.U > 1 && g_tune.cooperative) {
+    if (f.U > 1 && T.cooperative) {
         // Units wait for sibling units, so the whole grid must be resident at once.  Alone on the device it
         // is (the grid is sized for that); a cooperative launch makes the runtime guarantee it also when
         // another such launch is in flight on a different stream, where two half-resident grids could
@@ -541,28 +556,29 @@ cgbn_status launch_fused_kernel(KernelT kernel, const FusedPlan& f, FusedArgs& A
 
 // ACT: 0 plain, 1 ReLU, 2 shortcut + ReLU (forward only)
 template <typename T, bool FWD, int ACT>
-cgbn_status launch_fused_t(const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st, bool* taken, double moved_bytes)
+cgbn_status launch_fused_t(const Tuning& knobs, const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st, bool* taken,
+                           double moved_bytes)
 {
     *taken = false;
     if (f.big && f.LB == 16 && f.LPPC == 0) {
-        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, 0, ACT, 1>, f, A, sync_words, st, taken, moved_bytes);
-        else return launch_fused_kernel(nchw_fused_backward<T, 16, 0, ACT, 1>, f, A, sync_words, st, taken, moved_bytes);
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, 0, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes);
+        else return launch_fused_kernel(nchw_fused_backward<T, 16, 0, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes);
     }
     if (f.big && f.LB == 16 && f.LPPC == -2) {
-        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, -2, ACT, 1>, f, A, sync_words, st, taken, moved_bytes);
-        else return launch_fused_kernel(nchw_fused_backward<T, 16, -2, ACT, 1>, f, A, sync_words, st, taken, moved_bytes);
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, -2, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes);
+        else return launch_fused_kernel(nchw_fused_backward<T, 16, -2, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes);
     }
 #define CGBN_FUSED_CASE2(LB_, LPPC_)                                                                         \
     if (f.big == 2 && f.LB == LB_ && f.LPPC == LPPC_) {                                                      \
-        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 2>, f, A, sync_words, st, taken, moved_bytes); \
-        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 2>, f, A, sync_words, st, taken, moved_bytes); \
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 2>, knobs, f, A, sync_words, st, taken, moved_bytes); \
+        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 2>, knobs, f, A, sync_words, st, taken, moved_bytes); \
     }
     CGBN_FUSED_BIG_SMALL(CGBN_FUSED_CASE2)
 #undef CGBN_FUSED_CASE2
 #define CGBN_FUSED_CASE(LB_, LPPC_)                                                                          \
     if (f.LB == LB_ && f.LPPC == LPPC_) {                                                                    \
-        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 0>, f, A, sync_words, st, taken, moved_bytes); \
-        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 0>, f, A, sync_words, st, taken, moved_bytes); \
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 0>, knobs, f, A, sync_words, st, taken, moved_bytes); \
+        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 0>, knobs, f, A, sync_words, st, taken, moved_bytes); \
     }
     CGBN_FUSED_COMMON(CGBN_FUSED_CASE)
     if constexpr (FWD) {
@@ -588,8 +604,9 @@ FusedArgs fused_args(const Plan& p, const FusedPlan& f, char* ws)
     A.M = p.M; A.inv_M_f64 = 1.0 / p.M; A.shard_count = p.M / p.K; A.inv_M = (float)(1.0 / p.M);
     A.N = p.N; A.C = p.C; A.HW = p.HW; A.rows = f.rows; A.K = p.K; A.rps = f.rps; A.G = f.G;
     A.U = f.U; A.tp = f.tp; A.TL = f.TL; A.LPP = f.LPP; A.IPU = f.IPU;
-    A.nt = (int)g_tune.nt_store;
-    A.spin_limit = (unsigned)g_tune.spin_limit;
+    A.nt = (int)p.t.nt_store;
+    A.spin_limit = (unsigned)p.t.spin_limit;
+    A.wait_ticks = (unsigned long long)p.t.wait_us * 100ull;          // the wall clock counts at 100 MHz
     A.plane_stride = (unsigned)((long long)p.C * p.HW * p.eb);
 #ifdef CGBN_TRACE
     A.trace = g_trace;
@@ -612,15 +629,15 @@ extern "C" {
 size_t cgbn_workspace_bytes(int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype, int K)
 {
     Plan p;
-    if (make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return 0;
+    if (make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return 0;
     return p.bytes;
 }
 
 size_t cgbn_workspace_error_offset(int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype, int K)
 {
     Plan p;
-    if (make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return (size_t)-1;
-    return p.off_sync + sizeof(unsigned);
+    if (make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return (size_t)-1;
+    return kErrorWordOffset;
 }
 
 cgbn_status cgbn_shard_sum(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
@@ -628,7 +645,7 @@ cgbn_status cgbn_shard_sum(const void* x, int N, int C, int H, int W, cgbn_layou
 {
     if (!x || !s) return CGBN_ERR_NULL;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    CGBN_TRY(make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, K, &p));
     if (!aligned16(x)) return CGBN_ERR_ALIGN;
     CGBN_TRY(check_ws(p, workspace, workspace_bytes));
     char* ws = static_cast<char*>(workspace);
@@ -657,7 +674,7 @@ cgbn_status cgbn_shard_sqdev(const void* x, int N, int C, int H, int W, cgbn_lay
 {
     if (!x || !mean || !v) return CGBN_ERR_NULL;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    CGBN_TRY(make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, K, &p));
     if (!aligned16(x)) return CGBN_ERR_ALIGN;
     CGBN_TRY(check_ws(p, workspace, workspace_bytes));
     char* ws = static_cast<char*>(workspace);
@@ -687,7 +704,7 @@ cgbn_status cgbn_normalize(const void* x, int N, int C, int H, int W, cgbn_layou
 {
     if (!x || !mean || !invstd || !gamma || !beta || !y) return CGBN_ERR_NULL;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, 1, &p));
+    CGBN_TRY(make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, 1, &p));
     if (!aligned16(x) || !aligned16(y)) return CGBN_ERR_ALIGN;
     SweepArgs A = sweep_args(p);
     A.x = x; A.out = y; A.mean = mean; A.mean_lo = mean_lo; A.invstd = invstd; A.gamma = gamma; A.beta = beta;
@@ -701,7 +718,7 @@ cgbn_status cgbn_backward_shard_sums(const void* dy, const void* x, int N, int C
 {
     if (!dy || !x || !mean || !invstd || !a || !b) return CGBN_ERR_NULL;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    CGBN_TRY(make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, K, &p));
     if (!aligned16(x) || !aligned16(dy)) return CGBN_ERR_ALIGN;
     CGBN_TRY(check_ws(p, workspace, workspace_bytes));
     char* ws = static_cast<char*>(workspace);
@@ -734,7 +751,7 @@ cgbn_status cgbn_backward_dx(const void* dy, const void* x, int N, int C, int H,
 {
     if (!dy || !x || !mean || !invstd || !gamma || !dgamma || !dbeta || !dx) return CGBN_ERR_NULL;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, 1, &p));
+    CGBN_TRY(make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, 1, &p));
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dx)) return CGBN_ERR_ALIGN;
     SweepArgs A = sweep_args(p);
     A.x = x; A.dy = dy; A.out = dx; A.mean = mean; A.mean_lo = mean_lo; A.invstd = invstd;
@@ -748,7 +765,7 @@ cgbn_status cgbn_frozen_forward(const void* x, int N, int C, int H, int W, cgbn_
 {
     if (!x || !fixed_mean || !fixed_var || !gamma || !beta || !y) return CGBN_ERR_NULL;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, 1, &p));
+    CGBN_TRY(make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, 1, &p));
     if (!eps_ok(eps)) return CGBN_ERR_EPS;
     if (!aligned16(x) || !aligned16(y)) return CGBN_ERR_ALIGN;
     SweepArgs A = sweep_args(p);
@@ -761,7 +778,7 @@ cgbn_status cgbn_frozen_backward(const void* dy, int N, int C, int H, int W, cgb
 {
     if (!dy || !fixed_var || !gamma || !dx) return CGBN_ERR_NULL;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, 1, &p));
+    CGBN_TRY(make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, 1, &p));
     if (!eps_ok(eps)) return CGBN_ERR_EPS;
     if (!aligned16(dy) || !aligned16(dx)) return CGBN_ERR_ALIGN;
     SweepArgs A = sweep_args(p);
@@ -789,14 +806,14 @@ cgbn_status cgbn_update_running_stats(const float* mean, const float* mean_lo, c
 namespace {
 
 // Algorithm 1, optionally followed by "+ shortcut" and a ReLU (relu == true)
-cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, int C, int H, int W,
+cgbn_status forward_impl(const Tuning& T, const void* x, const void* shortcut, bool relu, int N, int C, int H, int W,
                          cgbn_layout layout, int K, const float* gamma, const float* beta, float eps,
                          void* y, float* mean, float* invstd, cgbn_dtype dtype, float* mean_lo,
                          void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!x || !gamma || !beta || !y || !mean || !invstd) return CGBN_ERR_NULL;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    CGBN_TRY(make_plan(T, N, C, H, W, (int)layout, (int)dtype, K, &p));
     if (!eps_ok(eps)) return CGBN_ERR_EPS;
     if (!aligned16(x) || !aligned16(y) || !aligned16(shortcut)) return CGBN_ERR_ALIGN;
     CGBN_TRY(check_ws(p, workspace, workspace_bytes));
@@ -805,9 +822,9 @@ cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, 
     float* part0 = reinterpret_cast<float*>(ws + p.off_part0);
     double* sh0 = reinterpret_cast<double*>(ws + p.off_sh0);
     float* mlo = reinterpret_cast<float*>(ws + p.off_mlo);
-    const int rev = (int)g_tune.reverse;
+    const int rev = (int)p.t.reverse;
 
-    if (g_tune.fused && p.ff.ok) {
+    if (p.t.fused && p.ff.ok) {
         FusedArgs F = fused_args(p, p.ff, ws);
         F.x = x; F.out = y; F.gamma = gamma; F.beta = beta; F.eps = (double)eps; F.aux = shortcut;
         F.mean = mean; F.mean_lo = mlo; F.mean_lo_user = mean_lo; F.invstd = invstd;
@@ -815,12 +832,12 @@ cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, 
         const int sync_words = kSyncHeader + 4 * p.C;
         const bool f32 = p.dtype == CGBN_F32;
         const double moved = (double)p.S * p.eb * (shortcut ? 3.0 : 2.0);
-        cgbn_status st_ = relu && shortcut ? (f32 ? launch_fused_t<float, true, 2>(p.ff, F, sync_words, st, &taken, moved)
-                                                  : launch_fused_t<bf16_t, true, 2>(p.ff, F, sync_words, st, &taken, moved))
-                        : relu ? (f32 ? launch_fused_t<float, true, 1>(p.ff, F, sync_words, st, &taken, moved)
-                                      : launch_fused_t<bf16_t, true, 1>(p.ff, F, sync_words, st, &taken, moved))
-                               : (f32 ? launch_fused_t<float, true, 0>(p.ff, F, sync_words, st, &taken, moved)
-                                      : launch_fused_t<bf16_t, true, 0>(p.ff, F, sync_words, st, &taken, moved));
+        cgbn_status st_ = relu && shortcut ? (f32 ? launch_fused_t<float, true, 2>(p.t, p.ff, F, sync_words, st, &taken, moved)
+                                                  : launch_fused_t<bf16_t, true, 2>(p.t, p.ff, F, sync_words, st, &taken, moved))
+                        : relu ? (f32 ? launch_fused_t<float, true, 1>(p.t, p.ff, F, sync_words, st, &taken, moved)
+                                      : launch_fused_t<bf16_t, true, 1>(p.t, p.ff, F, sync_words, st, &taken, moved))
+                               : (f32 ? launch_fused_t<float, true, 0>(p.t, p.ff, F, sync_words, st, &taken, moved)
+                                      : launch_fused_t<bf16_t, true, 0>(p.t, p.ff, F, sync_words, st, &taken, moved));
         g_last_forward_fused = taken;
         if (taken || st_ != CGBN_OK) return st_;
     }
@@ -828,7 +845,7 @@ cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, 
 
     SweepArgs A = sweep_args(p);
     A.x = x; A.part0 = part0;
-    if (g_tune.one_sweep_stats) {
+    if (p.t.one_sweep_stats) {
         // Not Algorithm 1: one sweep leaves every shard's (count, mean, M2), merged pairwise into the
         // pooled statistics; then step 11 as usual.  3 sweeps of the tensor instead of 4.
         A.part1 = reinterpret_cast<float*>(ws + p.off_part1);
@@ -853,7 +870,7 @@ cgbn_status forward_impl(const void* x, const void* shortcut, bool relu, int N, 
 
 // The backward; with `y` (the stored output of the ReLU variant) dy is first masked by y > 0
 // and `dshortcut`, if not null, receives the masked dy.
-cgbn_status backward_impl(const void* dy, const void* y, const void* x, const float* mean, const float* invstd,
+cgbn_status backward_impl(const Tuning& T, const void* dy, const void* y, const void* x, const float* mean, const float* invstd,
                           const float* gamma, void* dx, void* dshortcut, float* dgamma, float* dbeta,
                           int N, int C, int H, int W, cgbn_layout layout, int K,
                           cgbn_dtype dtype, const float* mean_lo,
@@ -862,15 +879,15 @@ cgbn_status backward_impl(const void* dy, const void* y, const void* x, const fl
     if (!dy || !x || !mean || !invstd || !gamma || !dx || !dgamma || !dbeta) return CGBN_ERR_NULL;
     const bool relu = y != nullptr;
     Plan p;
-    CGBN_TRY(make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p));
+    CGBN_TRY(make_plan(T, N, C, H, W, (int)layout, (int)dtype, K, &p));
     if (!aligned16(x) || !aligned16(dy) || !aligned16(dx) || !aligned16(y) || !aligned16(dshortcut)) return CGBN_ERR_ALIGN;
     if (dshortcut && dshortcut == dx) return CGBN_ERR_ALIAS;
     CGBN_TRY(check_ws(p, workspace, workspace_bytes));
     char* ws = static_cast<char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int rev = (int)g_tune.reverse;
+    const int rev = (int)p.t.reverse;
 
-    if (g_tune.fused && p.fb.ok) {
+    if (p.t.fused && p.fb.ok) {
         FusedArgs F = fused_args(p, p.fb, ws);
         F.x = x; F.dy = dy; F.out = dx; F.gamma = gamma; F.aux = y; F.out2 = dshortcut;
         F.mean = const_cast<float*>(mean); F.mean_lo = const_cast<float*>(mean_lo);
@@ -879,10 +896,10 @@ cgbn_status backward_impl(const void* dy, const void* y, const void* x, const fl
         const int sync_words = kSyncHeader + 4 * p.C;
         const bool f32 = p.dtype == CGBN_F32;
         const double moved = (double)p.S * p.eb * (3.0 + (relu ? 1.0 : 0.0) + (dshortcut ? 1.0 : 0.0));
-        cgbn_status st_ = relu ? (f32 ? launch_fused_t<float, false, 1>(p.fb, F, sync_words, st, &taken, moved)
-                                      : launch_fused_t<bf16_t, false, 1>(p.fb, F, sync_words, st, &taken, moved))
-                               : (f32 ? launch_fused_t<float, false, 0>(p.fb, F, sync_words, st, &taken, moved)
-                                      : launch_fused_t<bf16_t, false, 0>(p.fb, F, sync_words, st, &taken, moved));
+        cgbn_status st_ = relu ? (f32 ? launch_fused_t<float, false, 1>(p.t, p.fb, F, sync_words, st, &taken, moved)
+                                      : launch_fused_t<bf16_t, false, 1>(p.t, p.fb, F, sync_words, st, &taken, moved))
+                               : (f32 ? launch_fused_t<float, false, 0>(p.t, p.fb, F, sync_words, st, &taken, moved)
+                                      : launch_fused_t<bf16_t, false, 0>(p.t, p.fb, F, sync_words, st, &taken, moved));
         g_last_backward_fused = taken;
         if (taken || st_ != CGBN_OK) return st_;
     }
@@ -912,7 +929,7 @@ cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout 
                          cgbn_dtype dtype, float* mean_lo,
                          void* workspace, size_t workspace_bytes, void* stream)
 {
-    return forward_impl(x, nullptr, false, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, dtype, mean_lo,
+    return forward_impl(tuning_now(), x, nullptr, false, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, dtype, mean_lo,
                         workspace, workspace_bytes, stream);
 }
 
@@ -922,7 +939,7 @@ cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, cons
                           cgbn_dtype dtype, const float* mean_lo,
                           void* workspace, size_t workspace_bytes, void* stream)
 {
-    return backward_impl(dy, nullptr, x, mean, invstd, gamma, dx, nullptr, dgamma, dbeta, N, C, H, W, layout, K,
+    return backward_impl(tuning_now(), dy, nullptr, x, mean, invstd, gamma, dx, nullptr, dgamma, dbeta, N, C, H, W, layout, K,
                          dtype, mean_lo, workspace, workspace_bytes, stream);
 }
 
@@ -931,7 +948,7 @@ cgbn_status cgbn_forward_relu(const void* x, const void* shortcut, int N, int C,
                               void* y, float* mean, float* invstd, cgbn_dtype dtype, float* mean_lo,
                               void* workspace, size_t workspace_bytes, void* stream)
 {
-    return forward_impl(x, shortcut, true, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, dtype, mean_lo,
+    return forward_impl(tuning_now(), x, shortcut, true, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, dtype, mean_lo,
                         workspace, workspace_bytes, stream);
 }
 
@@ -942,8 +959,17 @@ cgbn_status cgbn_backward_relu(const void* dy, const void* y, const void* x, con
                                void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!y) return CGBN_ERR_NULL;
-    return backward_impl(dy, y, x, mean, invstd, gamma, dx, dshortcut, dgamma, dbeta, N, C, H, W, layout, K,
+    return backward_impl(tuning_now(), dy, y, x, mean, invstd, gamma, dx, dshortcut, dgamma, dbeta, N, C, H, W, layout, K,
                          dtype, mean_lo, workspace, workspace_bytes, stream);
+}
+
+cgbn_status cgbn_workspace_status(const void* workspace, int* gave_up, void* stream)
+{
+    if (!workspace || !gave_up) return CGBN_ERR_NULL;
+    if (((uintptr_t)workspace & 255u) != 0) return CGBN_ERR_WORKSPACE;
+    hipLaunchKernelGGL(error_word_to_flag, dim3(1), dim3(kWave), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const unsigned*>(workspace), gave_up);
+    return launched();
 }
 
 const char* cgbn_status_string(cgbn_status status)
@@ -983,6 +1009,7 @@ static long long* tuning_slot(const char* key)
     if (!std::strcmp(key, "stagger")) return &g_tune.stagger;
     if (!std::strcmp(key, "stagger_us")) return &g_tune.stagger_us;
     if (!std::strcmp(key, "stagger_phases")) return &g_tune.stagger_phases;
+    if (!std::strcmp(key, "wait_us")) return &g_tune.wait_us;
     return nullptr;
 }
 
@@ -999,6 +1026,8 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
         if (value < 0 || value > 1000) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.stagger_phases) {
         if (value < 2 || value > 64) return CGBN_ERR_TUNING;
+    } else if (slot == &g_tune.wait_us) {
+        if (value < 1 || value > 60000000LL) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.fused_groups) {
         if (value < 0 || value > (1LL << 20)) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.wave_plane_bytes) {
@@ -1008,6 +1037,7 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
     } else if (value < 4096 || value > (1LL << 26)) {
         return CGBN_ERR_TUNING;
     }
+    std::lock_guard<std::mutex> hold(g_tune_lock);
     *slot = value;
     return CGBN_OK;
 }
@@ -1031,7 +1061,7 @@ cgbn_status cgbn_calibration_copy(const void* src, void* dst, size_t bytes, void
 long long cgbn_plan_get(int N, int C, int H, int W, cgbn_layout layout, cgbn_dtype dtype, int K, const char* key)
 {
     Plan p;
-    if (!key || make_plan(N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return -1;
+    if (!key || make_plan(tuning_now(), N, C, H, W, (int)layout, (int)dtype, K, &p) != CGBN_OK) return -1;
     const bool bwd = !std::strncmp(key, "bwd_", 4);
     if (bwd || !std::strncmp(key, "fwd_", 4)) {
         const FusedPlan& f = bwd ? p.fb : p.ff;
@@ -1075,10 +1105,12 @@ long long cgbn_plan_get(int N, int C, int H, int W, cgbn_layout layout, cgbn_dty
 
 long long cgbn_get_tuning(const char* key)
 {
-    if (key && !std::strcmp(key, "last_forward_fused")) return g_last_forward_fused;
-    if (key && !std::strcmp(key, "last_backward_fused")) return g_last_backward_fused;
+    if (key && !std::strcmp(key, "last_forward_fused")) return g_last_forward_fused.load();
+    if (key && !std::strcmp(key, "last_backward_fused")) return g_last_backward_fused.load();
     long long* slot = tuning_slot(key);
-    return slot ? *slot : -1;
+    if (!slot) return -1;
+    std::lock_guard<std::mutex> hold(g_tune_lock);
+    return *slot;
 }
 
 }  // extern "C"

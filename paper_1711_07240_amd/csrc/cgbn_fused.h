@@ -55,6 +55,7 @@ namespace cgbn {
 
 constexpr int kFusedWords = 128;          // 32-bit registers of unit data per thread
 constexpr int kSyncHeader = 64;           // words before the per-channel arrays in the sync area
+constexpr size_t kErrorWordOffset = sizeof(unsigned);   // the sync area opens the workspace; its word 1 is the error word
 constexpr int kFusedLdsWords = 24;        // further 32-bit words of unit data per thread kept in LDS (large planes, 16-byte loads)
 constexpr int kFusedMaxRows = 2048;       // rows of a channel staged in LDS by the reducing workgroup
 constexpr int kFusedMaxShards = 512;
@@ -104,11 +105,19 @@ struct FusedArgs {
     int LPP, IPU;         // small planes: loads per lane and plane, images per unit
     int nt;
     unsigned spin_limit;
+    unsigned long long wait_ticks;            // 100 MHz ticks after which a wait gives up
     unsigned stagger_ticks, stagger_phases;   // start-up delay between channel slots (100 MHz ticks; 0 = none)
     unsigned plane_stride; // small planes: bytes between the same channel's planes of consecutive images
 };
 
 constexpr unsigned kRowSentinel = 0xffffffffu;
+
+// For callers that want to learn of a give-up without reading the workspace themselves: raises *flag (a
+// device int the caller zeroed at some earlier point) if the workspace's error word is set.
+static __global__ void error_word_to_flag(const unsigned* sync, int* flag)
+{
+    if (threadIdx.x == 0 && blockIdx.x == 0 && sync[1] != 0u) *flag = 1;
+}
 
 // Before every launch: clear the error word and mark every row "not written yet".
 static __global__ __launch_bounds__(kThreads) void fused_init(unsigned* sync, int sync_words, unsigned* rows, long long row_words)
@@ -273,6 +282,7 @@ template <int BIG> struct ReduceLdsT {
     double shard[2][BIG == 2 ? kFusedMaxShardsBigSmall : BIG == 1 ? kFusedMaxShardsBig : kFusedMaxShards];
     float stat[2];        // the reduced statistics, broadcast to the workgroup
     int missing;          // some row was still the sentinel in this poll
+    int gave_up;          // lane 0 has stopped waiting: this poll is the last
 };
 
 enum { ST_MEAN = 0, ST_INVSTD = 1, ST_SUMS = 2 };
@@ -306,7 +316,12 @@ __device__ __forceinline__ void count_in(unsigned* cnt, unsigned* flag, int U)
 // workgroups put next to no load on the memory system), then fetches the Q row
 // arrays of channel c into LDS, again until no sentinel is left (a row store may
 // still be in flight when the flag is seen).
-// Bounded: false if `spin_limit` polls were not enough.
+// Every wait ends: lane 0 gives up on the flag after `spin_limit` polls or `wait_ticks` of
+// wall-clock time, and at once when the launch's error word is already up (some wait has
+// given up before: the grid is not resident as assumed, and waiting again would only burn
+// time).  After giving up, the rows are fetched once more and decide by themselves: they are
+// their own validity flags, so if none is a sentinel the statistics are sound.  Otherwise
+// the error word is set and false returned (the caller poisons its statistics).
 // Row r of the first array is rows0[r * stride] (rows1 likewise, used if Q == 2).
 template <int Q, class LDS>
 __device__ __forceinline__ bool gather_rows(const FusedArgs& A, const float* rows0, const float* rows1, int stride,
@@ -315,17 +330,25 @@ __device__ __forceinline__ bool gather_rows(const FusedArgs& A, const float* row
     const int t = threadIdx.x;
     const unsigned* p0 = reinterpret_cast<const unsigned*>(rows0);
     const unsigned* p1 = reinterpret_cast<const unsigned*>(rows1);
-    unsigned polls = 0;
+    int gave_up = 0;                  // lane 0's own verdict
+    unsigned long long t0 = 0;
     if (t == 0) {
-        while (ld_agent(flag) == 0u && polls < A.spin_limit) {
+        t0 = wall_clock64();
+        for (unsigned polls = 0;; ++polls) {
+            if (polls >= A.spin_limit) { gave_up = 1; break; }
+            if (ld_agent(flag) != 0u) break;
+            if ((polls & 31u) == 31u && (ld_agent(A.sync + 1) != 0u || wall_clock64() - t0 > A.wait_ticks)) { gave_up = 1; break; }
             __builtin_amdgcn_s_sleep(2);
-            ++polls;
         }
     }
     for (unsigned tries = 0;; ++tries) {
-        int missing = (t == 0 && polls >= A.spin_limit) ? 1 : 0;      // lane 0 gave up on the flag
-        if (t == 0) L.missing = 0;
-        __syncthreads();              // lane 0 has seen the count; LDS rows are free to overwrite
+        int missing = 0;
+        if (t == 0) {
+            if (tries >= A.spin_limit || (tries > 0 && wall_clock64() - t0 > A.wait_ticks)) gave_up = 1;
+            L.missing = 0;
+            L.gave_up = gave_up;
+        }
+        __syncthreads();              // lane 0 has seen the flag; LDS rows are free to overwrite
         for (int r = t; r < A.rows; r += kThreads) {
             unsigned b0 = ld_agent(p0 + (size_t)r * stride);
             missing |= b0 == kRowSentinel;
@@ -338,10 +361,10 @@ __device__ __forceinline__ bool gather_rows(const FusedArgs& A, const float* row
         }
         if (missing) L.missing = 1;
         __syncthreads();
-        const int any_missing = L.missing;
+        const int any_missing = L.missing, stop = L.gave_up;
         __syncthreads();              // everyone has read the verdict before it is reset
         if (!any_missing) return true;
-        if (tries >= A.spin_limit) {
+        if (stop) {
             if (t == 0) atomicExch(A.sync + 1, 1u);
             return false;
         }

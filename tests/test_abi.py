@@ -129,3 +129,69 @@ def test_tuning_knobs():
         assert L.cgbn_workspace_bytes(16, 64, 400, 672, "NCHW", "f32", 8) < before
     finally:
         L.cgbn_set_tuning("chunk_bytes", old)
+
+
+def test_knob_changed_between_sizing_and_call_is_refused_not_overrun():
+    """A workspace sized under one set of knobs is too small under another: the call says so before any launch."""
+    shape = (16, 64, 400, 672)
+    wb = L.cgbn_workspace_bytes(*shape, "NCHW", "f32", 8)
+    old = L.cgbn_get_tuning("chunk_bytes")
+    try:
+        L.cgbn_set_tuning("chunk_bytes", 4096)               # many more row partials per channel
+        assert L.cgbn_workspace_bytes(*shape, "NCHW", "f32", 8) > wb
+        a = dict(GOOD, N=16, C=64, H=400, W=672, K=8, workspace_bytes=wb)
+        with pytest.raises(L.CgbnError) as e:
+            L.cgbn_forward(**a)
+        assert e.value.code == 6
+    finally:
+        L.cgbn_set_tuning("chunk_bytes", old)
+    assert L.cgbn_workspace_bytes(*shape, "NCHW", "f32", 8) == wb
+
+
+def test_calls_see_one_consistent_copy_of_the_knobs_under_concurrent_changes():
+    """One thread flips a knob that the workspace size depends on while others size workspaces: every answer
+    is the size under one setting or under the other, never a mixture, and nothing crashes."""
+    import threading
+    shape = (8, 48, 300, 500, "NCHW", "f32", 4)
+    old = L.cgbn_get_tuning("chunk_bytes")
+    sizes = {}
+    for v in (8192, 65536):
+        L.cgbn_set_tuning("chunk_bytes", v)
+        sizes[v] = (L.cgbn_workspace_bytes(*shape), L.cgbn_plan_get(*shape, "rows"))
+    assert sizes[8192] != sizes[65536]
+    stop, bad = threading.Event(), []
+
+    def flip():
+        i = 0
+        while not stop.is_set():
+            L.cgbn_set_tuning("chunk_bytes", (8192, 65536)[i & 1])
+            i += 1
+
+    def size():
+        ok_bytes, ok_rows = {s[0] for s in sizes.values()}, {s[1] for s in sizes.values()}
+        for _ in range(3000):
+            b, r = L.cgbn_workspace_bytes(*shape), L.cgbn_plan_get(*shape, "rows")
+            if b not in ok_bytes or r not in ok_rows:
+                bad.append((b, r))
+
+    try:
+        th = [threading.Thread(target=flip)] + [threading.Thread(target=size) for _ in range(3)]
+        for t in th:
+            t.start()
+        for t in th[1:]:
+            t.join()
+        stop.set()
+        th[0].join()
+    finally:
+        L.cgbn_set_tuning("chunk_bytes", old)
+    assert not bad, bad[:3]
+
+
+def test_workspace_status_argument_errors_and_fixed_error_offset():
+    assert L.cgbn_workspace_error_offset(4, 16, 32, 32, "NCHW", "f32", 2) == 4
+    assert L.cgbn_workspace_error_offset(64, 512, 50, 84, "NHWC", "bf16", 32) == 4
+    for kw, code in ((dict(workspace=None, gave_up=P), 1), (dict(workspace=P, gave_up=None), 1),
+                     (dict(workspace=P + 64, gave_up=P), 6)):
+        with pytest.raises(L.CgbnError) as e:
+            L.cgbn_workspace_status(stream=0, **kw)
+        assert e.value.code == code

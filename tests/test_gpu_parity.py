@@ -409,26 +409,31 @@ def test_few_workgroups_walk_many_units(name, kw, groups, path):
         L.cgbn_set_tuning("stagger_us", 0)
 
 
-def test_bounded_wait_gives_up_cleanly(path):
+@pytest.mark.parametrize("knob,value", [("spin_limit", 0), ("wait_us", 1)])
+def test_bounded_wait_gives_up_cleanly(path, knob, value):
     """Failure handling of the single-launch kernels, forced from the host: with a
-    poll limit of zero a wait gives up unless its flag is already set.  The grid
-    must still drain, flag the error word and poison statistics with NaN rather
-    than return numbers computed from an incomplete reduction."""
+    poll limit of zero (or a time limit of a microsecond) a wait gives up unless the
+    rows it needs are already there.  The grid must still drain, flag the error word
+    and poison statistics with NaN rather than return numbers computed from an
+    incomplete reduction."""
     if not path:
         pytest.skip("the multi-sweep kernels have no device-side waits")
     wl = BASE.scaled(N=8, C=64, H=96, W=128, K=4)
     d = synth.make_inputs(wl)
     p = Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
     off = L.cgbn_workspace_error_offset(wl.N, wl.C, wl.H, wl.W, wl.layout, wl.dtype, wl.K)
-    old = L.cgbn_get_tuning("spin_limit")
+    old = L.cgbn_get_tuning(knob)
     try:
-        L.cgbn_set_tuning("spin_limit", 0)
+        L.cgbn_set_tuning(knob, value)
+        flag = torch.zeros(1, dtype=torch.int32, device=p.ws.device)
         p.forward()
+        L.cgbn_workspace_status(p.ws, flag)          # the caller's way to learn of it: a device int, raised if the word is up
         torch.cuda.synchronize()
         gave_up = int(p.ws[off:off + 4].view(torch.int32).item())
+        assert int(flag.item()) == gave_up
         r = p.results()
     finally:
-        L.cgbn_set_tuning("spin_limit", old)
+        L.cgbn_set_tuning(knob, old)
     ref = oracle_all(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype)
     assert gave_up in (0, 1)
     any_nan = bool(np.isnan(r["y"]).any() or np.isnan(r["mean"]).any() or np.isnan(r["invstd"]).any())
@@ -440,5 +445,8 @@ def test_bounded_wait_gives_up_cleanly(path):
     # and with the normal limit the same problem is clean
     p.forward(); p.backward()
     torch.cuda.synchronize()
-    assert int(p.ws[off:off + 4].view(torch.int32).item()) == 0
+    flag.fill_(7)
+    L.cgbn_workspace_status(p.ws, flag)
+    torch.cuda.synchronize()
+    assert int(p.ws[off:off + 4].view(torch.int32).item()) == 0 and int(flag.item()) == 7    # a clean word leaves the flag alone
     check_against_oracle(p.results(), ref, wl.dtype, "after the forced give-up")

@@ -74,7 +74,8 @@ enum {
     CGBN_ERR_HIP = 8,        /* the HIP runtime refused a launch */
     CGBN_ERR_TUNING = 9,     /* unknown tuning key or value out of range */
     CGBN_ERR_MOMENTUM = 10,  /* momentum outside [0, 1] */
-    CGBN_ERR_ALIAS = 11      /* two outputs that must differ are the same buffer */
+    CGBN_ERR_ALIAS = 11,     /* two outputs that must differ are the same buffer */
+    CGBN_ERR_SCRATCH = 12    /* cgbn_forward_static: the problem needs more than CGBN_STATIC_SCRATCH_BYTES */
 };
 
 typedef int cgbn_layout;
@@ -115,6 +116,28 @@ cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout 
                          void* y, float* mean, float* invstd,
                          cgbn_dtype dtype, float* mean_lo,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* cgbn_forward for callers that can neither allocate device memory nor bring a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * kernels and results as cgbn_forward, without `workspace` / `workspace_bytes`: the scratch is a
+ * static device array of CGBN_STATIC_SCRATCH_BYTES inside the library (each GPU the library runs
+ * on holds one until the process ends).  The call allocates and frees nothing, on the device or
+ * through any allocating library routine.
+ *   - A problem whose cgbn_workspace_bytes exceeds CGBN_STATIC_SCRATCH_BYTES is refused with
+ *     CGBN_ERR_SCRATCH before anything is launched (the five detector-shaped workloads of this
+ *     repository need 0.01 to 8.1 MiB).
+ *   - The array's device address is looked up on the first call on each device; make that call
+ *     outside a graph capture.
+ *   - Every call on a GPU uses that GPU's one array: calls that can overlap in time on one GPU
+ *     (different streams) race on it and must not be made; back-to-back calls on one stream are
+ *     fine (whatever must start cleared is cleared by kernels of the call itself).
+ *   - The give-up word of the single-launch kernels lives in the array too; there is no
+ *     workspace pointer to pass to cgbn_workspace_status, so watch it through NaN statistics. */
+#define CGBN_STATIC_SCRATCH_BYTES (16u << 20)
+cgbn_status cgbn_forward_static(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                                const float* gamma, const float* beta, float eps,
+                                void* y, float* mean, float* invstd,
+                                cgbn_dtype dtype, float* mean_lo, void* stream);
 
 /* Backward of Algorithm 1's last step through the pooled statistics.  In: dy, x,
  * mean[C], invstd[C] as written by cgbn_forward, gamma[C], mean_lo[C] or NULL.

@@ -33,6 +33,8 @@ SIGNATURES = {
     "cgbn_workspace_status": (_c_int, [_c_p, _c_p, _c_p]),
     "cgbn_forward": (_c_int, [_c_p] + [_c_int] * 4 + [_c_int, _c_int, _c_p, _c_p, _c_f,
                               _c_p, _c_p, _c_p, _c_int, _c_p, _c_p, _c_sz, _c_p]),
+    "cgbn_forward_static": (_c_int, [_c_p] + [_c_int] * 4 + [_c_int, _c_int, _c_p, _c_p, _c_f,
+                                     _c_p, _c_p, _c_p, _c_int, _c_p, _c_p]),
     "cgbn_backward": (_c_int, [_c_p] * 8 + [_c_int] * 4 + [_c_int, _c_int, _c_int, _c_p,
                                _c_p, _c_sz, _c_p]),
     "cgbn_forward_relu": (_c_int, [_c_p, _c_p] + [_c_int] * 4 + [_c_int, _c_int, _c_p, _c_p, _c_f,
@@ -142,6 +144,13 @@ def cgbn_forward(x, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd,
     _check(lib().cgbn_forward(_ptr(x), N, C, H, W, _enum(LAYOUTS, layout), K, _ptr(gamma), _ptr(beta),
                               float(eps), _ptr(y), _ptr(mean), _ptr(invstd), _enum(DTYPES, dtype),
                               _ptr(mean_lo), _ptr(workspace), wb, _stream(stream)), "cgbn_forward")
+
+
+def cgbn_forward_static(x, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd,
+                        dtype="f32", mean_lo=None, stream=None) -> None:
+    _check(lib().cgbn_forward_static(_ptr(x), N, C, H, W, _enum(LAYOUTS, layout), K, _ptr(gamma), _ptr(beta),
+                                     float(eps), _ptr(y), _ptr(mean), _ptr(invstd), _enum(DTYPES, dtype),
+                                     _ptr(mean_lo), _stream(stream)), "cgbn_forward_static")
 
 
 def cgbn_backward(dy, x, mean, invstd, gamma, dx, dgamma, dbeta, N, C, H, W, layout, K,

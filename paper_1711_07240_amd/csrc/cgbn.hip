@@ -50,9 +50,37 @@ CGBN_FUSED_BIG_SMALL(CGBN_DECL_B2)
 #undef CGBN_DECL_B
 }  // namespace cgbn
 
+// Scratch of cgbn_forward_static: one array per device, owned by the loaded library until the process ends.
+// In host code this name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[CGBN_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace cgbn;
+
+// The device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];
+std::mutex g_scratch_lock;
+cgbn_status scratch_of_current_device(void** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) {
+        (void)hipGetLastError();
+        return CGBN_ERR_HIP;
+    }
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return CGBN_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return CGBN_OK;
+}
 
 // ---- launch-shape knobs (cgbn_set_tuning) ---------------------------------
 struct Tuning {
@@ -933,6 +961,25 @@ cgbn_status cgbn_forward(const void* x, int N, int C, int H, int W, cgbn_layout 
                         workspace, workspace_bytes, stream);
 }
 
+cgbn_status cgbn_forward_static(const void* x, int N, int C, int H, int W, cgbn_layout layout, int K,
+                                const float* gamma, const float* beta, float eps,
+                                void* y, float* mean, float* invstd,
+                                cgbn_dtype dtype, float* mean_lo, void* stream)
+{
+    // every argument error is answered before the device is asked for anything
+    if (!x || !gamma || !beta || !y || !mean || !invstd) return CGBN_ERR_NULL;
+    const Tuning T = tuning_now();
+    Plan p;
+    CGBN_TRY(make_plan(T, N, C, H, W, (int)layout, (int)dtype, K, &p));
+    if (!eps_ok(eps)) return CGBN_ERR_EPS;
+    if (!aligned16(x) || !aligned16(y)) return CGBN_ERR_ALIGN;
+    if (p.bytes > (size_t)CGBN_STATIC_SCRATCH_BYTES) return CGBN_ERR_SCRATCH;
+    void* ws = nullptr;
+    CGBN_TRY(scratch_of_current_device(&ws));
+    return forward_impl(T, x, nullptr, false, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, dtype, mean_lo,
+                        ws, (size_t)CGBN_STATIC_SCRATCH_BYTES, stream);
+}
+
 cgbn_status cgbn_backward(const void* dy, const void* x, const float* mean, const float* invstd,
                           const float* gamma, void* dx, float* dgamma, float* dbeta,
                           int N, int C, int H, int W, cgbn_layout layout, int K,
@@ -987,6 +1034,7 @@ const char* cgbn_status_string(cgbn_status status)
     case CGBN_ERR_TUNING: return "unknown tuning key or value out of range";
     case CGBN_ERR_MOMENTUM: return "momentum outside [0, 1]";
     case CGBN_ERR_ALIAS: return "two outputs that must differ are the same buffer";
+    case CGBN_ERR_SCRATCH: return "the problem needs more scratch than the library's static array holds";
     }
     return "unknown status";
 }

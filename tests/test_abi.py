@@ -29,8 +29,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_status_strings():
-    seen = {L.cgbn_status_string(i) for i in range(12)}
-    assert len(seen) == 12 and "ok" in seen and "unknown status" not in seen
+    seen = {L.cgbn_status_string(i) for i in range(13)}
+    assert len(seen) == 13 and "ok" in seen and "unknown status" not in seen
     assert L.cgbn_status_string(99) == "unknown status"
 
 
@@ -195,3 +195,24 @@ def test_workspace_status_argument_errors_and_fixed_error_offset():
         with pytest.raises(L.CgbnError) as e:
             L.cgbn_workspace_status(stream=0, **kw)
         assert e.value.code == code
+
+
+def test_forward_static_argument_errors_and_size_limit():
+    """The entry point without a workspace: the usual argument errors, and a problem whose scratch would not
+    fit the library's static array is refused before anything touches a device."""
+    a = {k: v for k, v in GOOD.items() if k not in ("workspace", "workspace_bytes")}
+
+    def code(**kw):
+        with pytest.raises(L.CgbnError) as e:
+            L.cgbn_forward_static(**dict(a, **kw))
+        return e.value.code
+
+    assert code(x=None) == 1 and code(N=0) == 2 and code(K=3) == 3 and code(dtype=9) == 4 and code(eps=0.0) == 5
+    assert code(y=P + 4) == 7
+    limit = 16 << 20
+    big = dict(N=512, C=4096, H=20, W=21, K=256)            # 2 x (C x N floats) + 2 x (K x C doubles) > 16 MiB
+    assert L.cgbn_workspace_bytes(big["N"], big["C"], big["H"], big["W"], "NCHW", "f32", big["K"]) > limit
+    assert code(**big) == 12
+    for shape in [(4, 16, 32, 32, "NCHW", "f32", 2), (16, 64, 400, 672, "NCHW", "f32", 8), (16, 256, 200, 336, "NCHW", "f32", 8),
+                  (256, 2048, 25, 42, "NCHW", "f32", 128), (64, 512, 50, 84, "NHWC", "bf16", 32)]:
+        assert 0 < L.cgbn_workspace_bytes(*shape) <= limit

@@ -280,7 +280,9 @@ __device__ __forceinline__ void publish_row(float* p, float v)
 template <int BIG> struct ReduceLdsT {
     float rows[2][BIG ? kFusedMaxRowsBig : kFusedMaxRows];
     double shard[2][BIG == 2 ? kFusedMaxShardsBigSmall : BIG == 1 ? kFusedMaxShardsBig : kFusedMaxShards];
-    float stat[2];        // the reduced statistics, broadcast to the workgroup
+    double mean64;        // forward: the pooled mean before it is split into two floats
+    unsigned long long deadline;   // wall-clock value at which the current wait gives up
+    float stat[3];        // the reduced statistics, broadcast to the workgroup
     int missing;          // some row was still the sentinel in this poll
     int gave_up;          // lane 0 has stopped waiting: this poll is the last
 };
@@ -330,23 +332,22 @@ __device__ __forceinline__ bool gather_rows(const FusedArgs& A, const float* row
     const int t = threadIdx.x;
     const unsigned* p0 = reinterpret_cast<const unsigned*>(rows0);
     const unsigned* p1 = reinterpret_cast<const unsigned*>(rows1);
-    int gave_up = 0;                  // lane 0's own verdict
-    unsigned long long t0 = 0;
+    // (the deadline and lane 0's verdict live in LDS: next to a register-resident unit there is no register to spare)
     if (t == 0) {
-        t0 = wall_clock64();
+        L.deadline = wall_clock64() + A.wait_ticks;
+        L.gave_up = 0;
         for (unsigned polls = 0;; ++polls) {
-            if (polls >= A.spin_limit) { gave_up = 1; break; }
+            if (polls >= A.spin_limit) { L.gave_up = 1; break; }
             if (ld_agent(flag) != 0u) break;
-            if ((polls & 31u) == 31u && (ld_agent(A.sync + 1) != 0u || wall_clock64() - t0 > A.wait_ticks)) { gave_up = 1; break; }
+            if ((polls & 31u) == 31u && (ld_agent(A.sync + 1) != 0u || wall_clock64() > L.deadline)) { L.gave_up = 1; break; }
             __builtin_amdgcn_s_sleep(2);
         }
     }
     for (unsigned tries = 0;; ++tries) {
         int missing = 0;
         if (t == 0) {
-            if (tries >= A.spin_limit || (tries > 0 && wall_clock64() - t0 > A.wait_ticks)) gave_up = 1;
+            if (tries >= A.spin_limit || (tries > 0 && wall_clock64() > L.deadline)) L.gave_up = 1;
             L.missing = 0;
-            L.gave_up = gave_up;
         }
         __syncthreads();              // lane 0 has seen the flag; LDS rows are free to overwrite
         for (int r = t; r < A.rows; r += kThreads) {
@@ -426,6 +427,103 @@ __device__ __forceinline__ void reduce_rows(const FusedArgs& A, int c, LDS& L, d
     __syncthreads();
 }
 
+// The forward's reduction after its one hand-over.  rows[0] holds every row's s = sum(x - p), rows[1] its
+// q = sum(x - a)^2 (see row_centre / row_sqdev below).  Pass 1, steps 4-5: shard sums of s (written to sh0 with
+// the pivot added back), their total, the pooled mean in double precision (L.mean64; as two floats in
+// stat[0], stat[1]).  Pass 2, steps 6-10: every row's squared deviations from that mean, added shard by shard
+// (the device variance sums, written to sh1) and across shards; 1/sqrt(var + eps) in stat[2].  Same lane
+// layout and summation order as reduce_rows.  `count_of(r)`: elements in row r.
+template <class LDS, class RowCount>
+__device__ __forceinline__ void reduce_forward(const FusedArgs& A, int c, LDS& L, float pivot, bool write_shards,
+                                               RowCount count_of);
+
+// The forward hands over ONCE.  A unit holds its rows' data, so before the pooled mean is known it can
+// already form, for each row, s = sum(x - p) about the channel pivot p and q = sum(x - a)^2 about the row's
+// own centre a = p + s/n (a float: any number near the row's mean serves).  Once the pooled mean mu is
+// known, the row's part of Algorithm 1's device variance sum follows exactly, whatever a is:
+//     sum (x - mu)^2 = q + 2 (a - mu) sum(x - a) + n (a - mu)^2,      sum(x - a) = s - n (a - p),
+// all terms but q tiny or non-negative, so nothing cancels.  The reducing workgroup recomputes a from the
+// published s with the very operations the unit used (explicitly rounded, never contracted), so both
+// hold the same float.
+__device__ __forceinline__ float row_centre(float pivot, float s, float n)
+{
+    // the hardware reciprocal (one instruction, the same result wherever it runs on the chip), two rounded operations
+    return __fadd_rn(pivot, __fmul_rn(s, __builtin_amdgcn_rcpf(n)));
+}
+__device__ __forceinline__ double row_sqdev(float s, float q, double n, float pivot, double mean)
+{
+    const double a = (double)row_centre(pivot, s, (float)n);
+    const double d = a - mean;
+    const double r = (double)s - n * (a - (double)pivot);
+    return (double)q + d * (2.0 * r + n * d);
+}
+
+__device__ __forceinline__ double uniform_d(double v)
+{
+    const unsigned long long b = (unsigned long long)__double_as_longlong(v);
+    const unsigned lo = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)b);
+    const unsigned hi = (unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(b >> 32));
+    return __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));
+}
+
+template <class LDS, class RowCount>
+__device__ __forceinline__ void reduce_forward(const FusedArgs& A, int c, LDS& L, float pivot, bool write_shards,
+                                               RowCount count_of)
+{
+    const double shard_offset = (double)pivot * A.shard_count;
+    const int t = threadIdx.x, lane = t & (kWave - 1);
+    const int G = A.G, gl = t & (G - 1), gi = t / G, spb = kThreads / G;
+    for (int k0 = 0; k0 < A.K; k0 += spb) {
+        int k = k0 + gi;
+        double acc = 0.0;
+        if (k < A.K)
+            for (int r = gl; r < A.rps; r += G) acc += (double)L.rows[0][k * A.rps + r];
+        for (int off = G >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+        if (k < A.K && gl == 0) {
+            L.shard[0][k] = acc;
+            if (write_shards) A.sh0[(size_t)k * A.C + c] = acc + shard_offset;
+        }
+    }
+    __syncthreads();
+    if (t < kWave) {
+        double tot = 0.0;
+        for (int k = lane; k < A.K; k += kWave) tot += L.shard[0][k];
+        for (int off = kWave >> 1; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
+        if (lane == 0) {
+            const double m = (double)pivot + tot * A.inv_M_f64;
+            const float hi = (float)m;
+            L.mean64 = m;
+            L.stat[0] = hi;
+            L.stat[1] = (float)(m - (double)hi);
+        }
+    }
+    __syncthreads();
+    // (as scalars: next to a register-resident unit every vector register counts)
+    const double mean = uniform_d(L.mean64);
+    for (int k0 = 0; k0 < A.K; k0 += spb) {
+        int k = k0 + gi;
+        double acc = 0.0;
+        if (k < A.K)
+            for (int r = gl; r < A.rps; r += G) {
+                const int row = k * A.rps + r;
+                acc += row_sqdev(L.rows[0][row], L.rows[1][row], count_of(row), pivot, mean);
+            }
+        for (int off = G >> 1; off >= 1; off >>= 1) acc += __shfl_xor(acc, off);
+        if (k < A.K && gl == 0) {
+            L.shard[1][k] = acc;
+            if (write_shards) A.sh1[(size_t)k * A.C + c] = acc;
+        }
+    }
+    __syncthreads();
+    if (t < kWave) {
+        double tot = 0.0;
+        for (int k = lane; k < A.K; k += kWave) tot += L.shard[1][k];
+        for (int off = kWave >> 1; off >= 1; off >>= 1) tot += __shfl_xor(tot, off);
+        if (lane == 0) L.stat[2] = (float)rsqrt_f64(tot * A.inv_M_f64 + A.eps);
+    }
+    __syncthreads();
+}
+
 __device__ __forceinline__ int uniform(int v) { return __builtin_amdgcn_readfirstlane(v); }
 // A per-channel constant as a scalar register.  Besides saving a vector register this makes
 // the compiler wait for the constant's load HERE: left in a vector register, a value loaded
@@ -464,6 +562,17 @@ __device__ __forceinline__ void stagger_start(const FusedArgs& A)
     if (cls == 0u) return;
     const unsigned long long t0 = wall_clock64(), wait = (unsigned long long)cls * A.stagger_ticks;
     for (int i = 0; i < (1 << 16) && wall_clock64() - t0 < wait; ++i) __builtin_amdgcn_s_sleep(16);
+}
+
+// compile-time integers and a loop whose index is one (slot ranges must be constants: the slots are registers)
+template <int V> struct IntC { static constexpr int value = V; };
+template <bool V> struct BoolC { static constexpr bool value = V; };
+template <int N, int I = 0, class F> __device__ __forceinline__ void unroll_planes(F&& f)
+{
+    if constexpr (I < N) {
+        f(IntC<I>{});
+        unroll_planes<N, I + 1>(f);
+    }
 }
 
 // A unit's data is addressed as (uniform base pointer) + (32-bit per-lane byte
@@ -574,7 +683,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
     using SL = Slots<T, LB, LPPC, R, WGP ? RT / (WGP ? -LPPC : 1) : 1>;
     constexpr int SPW = WGP ? RT / SL::PPU : 1;
     __shared__ ReduceLdsT<BIG> lds;
-    __shared__ float s_red[4 * SL::PPU];
+    __shared__ float s_red[4 * SL::PPU], s_sq[4 * SL::PPU];
     const int t = threadIdx.x, lane = t & (kWave - 1), w = uniform(t >> 6);
     const T* x = static_cast<const T*>(A.x);
     const char* xb = static_cast<const char*>(A.x);
@@ -593,7 +702,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
         const int c = g.c;
         const char* xu = xb + g.base;
         char* yu = yb + g.base;
-        const float pivot = Elem<T>::load1(x + (long long)c * A.HW);
+        const float pivot = uniform_f(Elem<T>::load1(x + (long long)c * A.HW));
         CGBN_STAMP(0);
 
         // ---- read the unit once ------------------------------------------
@@ -612,160 +721,125 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             if (RL > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // the LDS slots have landed
         }
 
-        // ---- steps 1-3: sums about the pivot ------------------------------
+        // ---- steps 1-3 and 6-8 before the hand-over: per row, the sum about the pivot, then the squared
+        // deviations about the row's own centre (row_centre); both are published, and the reducing workgroups
+        // turn them into Algorithm 1's sums about the pooled mean (reduce_forward)
         {
             const unsigned loff = SL::lane_offset(t);
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
+            // one pass over the slots [s0, s1): the elements' sum of (x - centre), or of its square
+            auto pass = [&](auto s0_, auto s1_, float centre, auto square_) __attribute__((always_inline)) -> float {
+                constexpr int s0 = decltype(s0_)::value, s1 = decltype(s1_)::value;
+                constexpr bool square = decltype(square_)::value;
+                float acc[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < RT; ++s) {
-                if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
-                    uint32_t wv[W];
-                    if (s < RS) {
+                for (int s = s0; s < s1; ++s) {
+                    if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
+                        uint32_t wv[W];
+                        if (s < RS) {
 #pragma unroll
-                        for (int q = 0; q < W; ++q) wv[q] = d[(s < RS ? s : 0) * W + q];
-                    } else {
-                        LdsSlot<LB>::read(ext, s - RS, t, wv);
-                    }
+                            for (int q = 0; q < W; ++q) wv[q] = d[(s < RS ? s : 0) * W + q];
+                        } else {
+                            LdsSlot<LB>::read(ext, s - RS, t, wv);
+                        }
 #pragma unroll
-                    for (int q = 0; q < W; ++q) {
-                        float f[EPW];
-                        Packed<T>::unpack(wv[q], f);
+                        for (int q = 0; q < W; ++q) {
+                            float f[EPW];
+                            Packed<T>::unpack(wv[q], f);
 #pragma unroll
-                        for (int e = 0; e < EPW; ++e) acc[(q * EPW + e) & 3] += f[e] - pivot;
-                    }
-                }
-                if (SL::ends_plane(s)) {                    // plane complete: one row per plane
-                    int n = SL::image(g, s, w);
-                    if (n < g.n1) {
-                        float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                        if (lane == 0) {
-                            if (solo) lds.rows[0][n] = tot;
-                            else publish_row(&A.part0[(size_t)c * A.rows + n], tot);
+                            for (int e = 0; e < EPW; ++e) {
+                                const float dv = f[e] - centre;
+                                acc[(q * EPW + e) & 3] += square ? dv * dv : dv;
+                            }
                         }
                     }
-                    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
                 }
-                if (SL::ends_wg_plane(s)) {                 // a workgroup-wide plane is complete: its row
-                    const int pl = s / SPW, n = g.n0 + pl;
-                    float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                    if (lane == 0) s_red[4 * pl + w] = tot;
-                    __syncthreads();
-                    if (t == 0 && n < g.n1) {
-                        const float tot4 = (s_red[4 * pl] + s_red[4 * pl + 1]) + (s_red[4 * pl + 2] + s_red[4 * pl + 3]);
-                        if (solo) lds.rows[0][n] = tot4;
-                        else publish_row(&A.part0[(size_t)c * A.rows + n], tot4);
+                return wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
+            };
+            if constexpr (SMALL) {
+                // one plane per wavefront at a time: its row is the wavefront's own business
+                static_assert(RT % SL::SPP == 0, "whole planes only");
+                unroll_planes<RT / SL::SPP>([&](auto pl_) __attribute__((always_inline)) {
+                    constexpr int pl = decltype(pl_)::value, s0 = pl * SL::SPP;
+                    const int n = SL::image(g, s0, w);
+                    if (n < g.n1) {
+                        const float tot = pass(IntC<s0>{}, IntC<s0 + SL::SPP>{}, pivot, BoolC<false>{});
+                        const float ctr = row_centre(pivot, tot, (float)A.HW);
+                        const float sq = pass(IntC<s0>{}, IntC<s0 + SL::SPP>{}, ctr, BoolC<true>{});
+                        if (lane == 0) {
+                            if (solo) {
+                                lds.rows[0][n] = tot;
+                                lds.rows[1][n] = sq;
+                            } else {
+                                publish_row(&A.part0[(size_t)c * A.rows + n], tot);
+                                publish_row(&A.part1[(size_t)c * A.rows + n], sq);
+                            }
+                        }
                     }
-                    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
-                }
-            }
-            if (!SMALL && !WGP) {
-                float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                if (lane == 0) s_red[w] = tot;
-                __syncthreads();
-                if (t == 0) {
-                    const float tot4 = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
-                    if (solo) lds.rows[0][g.u] = tot4;
-                    else publish_row(&A.part0[(size_t)c * A.rows + g.u], tot4);
-                }
+                });
+            } else {
+                // a row per workgroup (a tile), or per workgroup-wide plane: the four wavefronts' sums meet in LDS,
+                // every thread adds them in the same order and so holds the same centre
+                unroll_planes<SL::PPU>([&](auto pl_) __attribute__((always_inline)) {
+                    constexpr int pl = decltype(pl_)::value;
+                    constexpr int s0 = WGP ? pl * SPW : 0, s1 = WGP ? (pl + 1) * SPW : RT;
+                    const int row = WGP ? g.n0 + pl : g.u;
+                    const bool live = !WGP || g.n0 + pl < g.n1;
+                    const float part = pass(IntC<s0>{}, IntC<s1>{}, pivot, BoolC<false>{});
+                    if (lane == 0) s_red[4 * pl + w] = part;
+                    __syncthreads();
+                    const float tot = (s_red[4 * pl] + s_red[4 * pl + 1]) + (s_red[4 * pl + 2] + s_red[4 * pl + 3]);
+                    const float count = (float)(WGP ? A.HW : g.len / (int)sizeof(T));
+                    const float ctr = row_centre(pivot, tot, count);
+                    const float part2 = pass(IntC<s0>{}, IntC<s1>{}, ctr, BoolC<true>{});
+                    if (lane == 0) s_sq[4 * pl + w] = part2;
+                    __syncthreads();
+                    if (t == 0 && live) {
+                        const float sq = (s_sq[4 * pl] + s_sq[4 * pl + 1]) + (s_sq[4 * pl + 2] + s_sq[4 * pl + 3]);
+                        if (solo) {
+                            lds.rows[0][row] = tot;
+                            lds.rows[1][row] = sq;
+                        } else {
+                            publish_row(&A.part0[(size_t)c * A.rows + row], tot);
+                            publish_row(&A.part1[(size_t)c * A.rows + row], sq);
+                        }
+                    }
+                });
             }
         }
         if (solo) __syncthreads();
         else count_in(A.sync + kSyncHeader + c, A.sync + kSyncHeader + 2 * A.C + c, A.U);
         CGBN_STAMP(1);
-        // ---- steps 4-5: when all rows are in, reduce them to the pooled mean
+        // ---- the one hand-over: when all rows are in, steps 4-5 and 9-10
         bool ok1 = false;
         // `rows > 0` always holds.  Keeping the hand-over in a block the compiler cannot
         // prove to run stops it from hoisting that block's index arithmetic out of the
         // unit loop, which would push the register-resident unit into scratch memory.
         if (A.rows > 0) {
-            ok1 = solo || gather_rows<1>(A, A.part0 + (size_t)c * A.rows, nullptr, 1, A.sync + kSyncHeader + 2 * A.C + c, lds);
+            ok1 = solo || gather_rows<2>(A, A.part0 + (size_t)c * A.rows, A.part1 + (size_t)c * A.rows, 1,
+                                         A.sync + kSyncHeader + 2 * A.C + c, lds);
             CGBN_STAMP(2);
-            reduce_rows<1, ST_MEAN>(A, c, lds, (double)pivot, g.u == 0);
+            if (SMALL || WGP) {
+                const double n_row = uniform_d((double)A.HW);
+                reduce_forward(A, c, lds, pivot, g.u == 0, [n_row](int) { return n_row; });
+            } else {
+                const int tp = A.tp, TL = A.TL, HW = A.HW;
+                reduce_forward(A, c, lds, pivot, g.u == 0, [tp, TL, HW](int row) {
+                    const int j = row % tp;
+                    return (double)min(TL, HW - j * TL);
+                });
+            }
         }
         CGBN_STAMP(3);
         float mu = uniform_f(lds.stat[0]);
         const float mulo = uniform_f(lds.stat[1]);
-        if (!ok1) mu = __uint_as_float(0x7fc00000u);
+        float istd = uniform_f(lds.stat[2]);
+        if (!ok1) mu = istd = __uint_as_float(0x7fc00000u);
         if (g.u == 0 && t == 0) {
             A.mean[c] = mu;
             A.mean_lo[c] = mulo;
             if (A.mean_lo_user) A.mean_lo_user[c] = mulo;
+            A.invstd[c] = istd;
         }
-
-        // ---- steps 6-8: squared deviations from the pooled mean -----------
-        {
-            const unsigned loff = SL::lane_offset(t);
-            float acc[4] = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int s = 0; s < RT; ++s) {
-                if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
-                    uint32_t wv[W];
-                    if (s < RS) {
-#pragma unroll
-                        for (int q = 0; q < W; ++q) wv[q] = d[(s < RS ? s : 0) * W + q];
-                    } else {
-                        LdsSlot<LB>::read(ext, s - RS, t, wv);
-                    }
-#pragma unroll
-                    for (int q = 0; q < W; ++q) {
-                        float f[EPW];
-                        Packed<T>::unpack(wv[q], f);
-#pragma unroll
-                        for (int e = 0; e < EPW; ++e) {
-                            float dv = (f[e] - mu) - mulo;
-                            acc[(q * EPW + e) & 3] += dv * dv;
-                        }
-                    }
-                }
-                if (SL::ends_plane(s)) {
-                    int n = SL::image(g, s, w);
-                    if (n < g.n1) {
-                        float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                        if (lane == 0) {
-                            if (solo) lds.rows[0][n] = tot;
-                            else publish_row(&A.part1[(size_t)c * A.rows + n], tot);
-                        }
-                    }
-                    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
-                }
-                if (SL::ends_wg_plane(s)) {
-                    const int pl = s / SPW, n = g.n0 + pl;
-                    float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                    if (lane == 0) s_red[4 * pl + w] = tot;
-                    __syncthreads();
-                    if (t == 0 && n < g.n1) {
-                        const float tot4 = (s_red[4 * pl] + s_red[4 * pl + 1]) + (s_red[4 * pl + 2] + s_red[4 * pl + 3]);
-                        if (solo) lds.rows[0][n] = tot4;
-                        else publish_row(&A.part1[(size_t)c * A.rows + n], tot4);
-                    }
-                    acc[0] = acc[1] = acc[2] = acc[3] = 0.f;
-                }
-            }
-            if (!SMALL && !WGP) {
-                float tot = wave_sum((acc[0] + acc[1]) + (acc[2] + acc[3]));
-                if (lane == 0) s_red[w] = tot;
-                __syncthreads();
-                if (t == 0) {
-                    const float tot4 = (s_red[0] + s_red[1]) + (s_red[2] + s_red[3]);
-                    if (solo) lds.rows[0][g.u] = tot4;
-                    else publish_row(&A.part1[(size_t)c * A.rows + g.u], tot4);
-                }
-            }
-        }
-        if (solo) __syncthreads();
-        else count_in(A.sync + kSyncHeader + A.C + c, A.sync + kSyncHeader + 3 * A.C + c, A.U);
-        CGBN_STAMP(4);
-        // ---- steps 9-10: reduce to the variance and 1/sqrt(var + eps)
-        bool ok2 = false;
-        if (A.rows > 0) {
-            ok2 = solo || gather_rows<1>(A, A.part1 + (size_t)c * A.rows, nullptr, 1, A.sync + kSyncHeader + 3 * A.C + c, lds);
-            CGBN_STAMP(5);
-            reduce_rows<1, ST_INVSTD>(A, c, lds, 0.0, g.u == 0, 1);
-        }
-        CGBN_STAMP(6);
-        float istd = uniform_f(lds.stat[0]);
-        if (!ok1 || !ok2) istd = __uint_as_float(0x7fc00000u);
-        if (g.u == 0 && t == 0) A.invstd[c] = istd;
 
         // ---- step 11: normalise from registers, write y --------------------
         if (ACT == 2) {

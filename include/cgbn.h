@@ -269,9 +269,11 @@ const char* cgbn_status_string(cgbn_status status);
  *   "nt_store"         0/1: non-temporal stores for y and dx
  *   "fused"            0/1: register-resident single-launch forward/backward (NCHW)
  *   "one_sweep_stats"  0/1 (default 0): where cgbn_forward runs as separate sweeps, take the statistics in ONE
- *                      sweep -- per-shard (count, mean, M2) about a per-channel pivot, merged pairwise -- instead
- *                      of Algorithm 1's two; same results up to rounding, 3 tensor sweeps instead of 4; loses
- *                      accuracy only if a channel's first value lies many standard deviations from its mean
+ *                      sweep -- per-shard (count, mean, M2) about a per-channel pivot (the channel's first value),
+ *                      merged pairwise -- instead of Algorithm 1's two; same results up to rounding, 3 tensor
+ *                      sweeps instead of 4.  Accurate while the pivot lies within about eleven standard deviations
+ *                      of the channel's mean; a channel where it does not gets NaN statistics and the workspace's
+ *                      error word is raised (cgbn_workspace_status), never a variance of unknown accuracy
  *   "cooperative"      0/1 (default 0): launch the single-launch kernels cooperatively, so that the runtime
  *                      guarantees the whole grid is resident; needed only if such calls can overlap on
  *                      different streams; costs about 15 us per launch

@@ -489,6 +489,10 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
     A.C = p.C; A.rows = p.rows; A.K = p.K; A.rps = p.rps; A.G = p.G;
     if (p.layout == CGBN_NCHW) { A.cs = p.rows; A.rs = 1; } else { A.cs = 1; A.rs = p.C; }
     A.clear_word = reinterpret_cast<unsigned*>(ws + p.off_sync) + 1;
+    if (mode == CM_MOMENTS) {       // this mode may raise the word: the sweep before it has cleared it
+        A.raise_word = A.clear_word;
+        A.clear_word = nullptr;
+    }
     dim3 grid((unsigned)((p.C + 3) / 4)), block(kThreads);
     switch (mode) {
     case CM_MEAN:   hipLaunchKernelGGL((combine_rows<CM_MEAN>), grid, block, 0, st, A); break;
@@ -877,7 +881,9 @@ cgbn_status forward_impl(const Tuning& T, const void* x, const void* shortcut, b
         // Not Algorithm 1: one sweep leaves every shard's (count, mean, M2), merged pairwise into the
         // pooled statistics; then step 11 as usual.  3 sweeps of the tensor instead of 4.
         A.part1 = reinterpret_cast<float*>(ws + p.off_part1);
+        A.clear_word = reinterpret_cast<unsigned*>(ws + p.off_sync) + 1;
         CGBN_TRY(launch_reduce(OP_MOMENTS, p, A, st));
+        A.clear_word = nullptr;
         CGBN_TRY(launch_combine(CM_MOMENTS, p, ws, mean, mlo, mean_lo, nullptr, nullptr, (double)eps, x, st, invstd));
         A.mean = mean; A.mean_lo = mlo; A.invstd = invstd; A.gamma = gamma; A.beta = beta; A.out = y;
         A.reverse = rev; A.dy = shortcut;

@@ -74,6 +74,8 @@ struct SweepArgs {
     float eps;                // fixed-statistics maps: `invstd` then points at variances
     int reverse;              // walk the grid backwards
     int nt;                   // non-temporal stores
+    unsigned* clear_word;     // reductions: set to zero if not null (the workspace's error word, where a later
+                              // kernel of the same call may raise it)
 };
 
 // --------------------------------------------------------------------------
@@ -411,6 +413,7 @@ __global__ __launch_bounds__(kThreads) void nchw_reduce_block(SweepArgs A)
     constexpr int VEC = Elem<T>::VEC;
     constexpr int Q = op_sums(OP);
     __shared__ float sm[2 * 4];
+    if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int j = (int)(b % A.sp);
     long long plane = b / A.sp;
@@ -445,6 +448,7 @@ __global__ __launch_bounds__(kThreads) void nchw_reduce_wave(SweepArgs A)
 {
     constexpr int VEC = Elem<T>::VEC;
     constexpr int Q = op_sums(OP);
+    if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
     long long plane = b * 4 + w;
@@ -523,6 +527,7 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
 {
     constexpr int Q = op_sums(OP);
     __shared__ float sm[Q * kThreads * V];
+    if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int ct = (int)(b % A.ctiles);
     int row = (int)(b / A.ctiles);
@@ -692,6 +697,8 @@ struct CombineArgs {
     int is_bf16;
     int C, rows, K, rps, G; // G lanes share one shard, a power of two <= 64
     unsigned* clear_word;   // set to zero if not null (the workspace's error word)
+    unsigned* raise_word;   // CM_MOMENTS: set to one when a channel's statistics cannot be vouched for (cleared by
+                            // the sweep before, never by this kernel)
 };
 
 __device__ __forceinline__ double pivot_of(const CombineArgs& A, int c)
@@ -758,8 +765,14 @@ __device__ __forceinline__ Moments merge_moments(const Moments& a, const Moments
 // the pivot p) -> all shards merged.  Shards are dealt to lane groups as in
 // shard_then_total; a lane merges its shards in order, then the 64 lanes merge in a
 // fixed tree (the lower lane always on the left).  Double precision throughout.
-__device__ __forceinline__ Moments merge_shard_moments(const float* p1, const float* p2, const CombineArgs& A, int lane)
+// A shard's M2 is formed as sum (x-p)^2 - n * mean^2: sound as long as the pivot lies within a
+// few spreads of the data, because the float rows of (x-p)^2 carry a rounding of about 1e-7
+// of THEIR size.  `raw` returns the channel's total of those rows, so that the caller can tell
+// when that rounding is no longer small against the pooled M2 (nothing is clamped here).
+__device__ __forceinline__ Moments merge_shard_moments(const float* p1, const float* p2, const CombineArgs& A, int lane,
+                                                       double* raw)
 {
+    double raw_mine = 0.0;
     const int G = A.G;
     const int gl = lane & (G - 1), gi = lane / G, spp = kWave / G;
     Moments mine = {0.0, 0.0, 0.0};
@@ -780,10 +793,12 @@ __device__ __forceinline__ Moments merge_shard_moments(const float* p1, const fl
             sk.n = A.shard_count;
             sk.mean = s1 / sk.n;                     // about the pivot
             sk.m2 = s2 - s1 * sk.mean;               // sum (x-p)^2 - n * mean^2
-            if (sk.m2 < 0.0) sk.m2 = 0.0;
+            raw_mine += s2;
             mine = merge_moments(mine, sk);
         }
     }
+    for (int off = kWave >> 1; off >= 1; off >>= 1) raw_mine += __shfl_xor(raw_mine, off);
+    *raw = raw_mine;
     for (int off = 1; off < kWave; off <<= 1) {
         Moments other;
         other.n = __shfl_xor(mine.n, off);
@@ -803,15 +818,25 @@ __global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
     if (c >= A.C) return;
     const double pivot = pivot_of(A, c);      // zero unless the rows hold sums about a pivot
     if (MODE == CM_MOMENTS) {
-        Moments m = merge_shard_moments(A.part0 + (size_t)c * A.cs, A.part1 + (size_t)c * A.cs, A, lane);
+        double raw = 0.0;
+        Moments m = merge_shard_moments(A.part0 + (size_t)c * A.cs, A.part1 + (size_t)c * A.cs, A, lane, &raw);
         if (lane != 0) return;
         double mean = pivot + m.mean;
         float hi = (float)mean;
         float lo = (float)(mean - (double)hi);
+        float istd = (float)(1.0 / sqrt((m.m2 > 0.0 ? m.m2 : 0.0) / A.M + A.eps));
+        // raw = M2 + M (mean - p)^2: when the pooled mean lies more than about eleven spreads from the pivot the
+        // rounding of the rows (1e-7 of raw) is no longer small against M2.  Then this one-sweep variant cannot
+        // keep its accuracy: it says so (error word, NaN statistics) instead of returning a variance it cannot
+        // vouch for.  (A negative M2 beyond rounding is the same condition.)
+        if (raw > 128.0 * m.m2 && raw > 0.0) {
+            hi = lo = istd = __uint_as_float(0x7fc00000u);
+            if (A.raise_word) atomicExch(A.raise_word, 1u);
+        }
         A.out0[c] = hi;
         A.out1[c] = lo;
         if (A.out2) A.out2[c] = lo;
-        A.out3[c] = (float)(1.0 / sqrt(m.m2 / A.M + A.eps));
+        A.out3[c] = istd;
         return;
     }
     double t0 = shard_then_total(A.part0 + (size_t)c * A.cs, A.sh0, c, A, lane, pivot * A.shard_count);

@@ -28,8 +28,23 @@ def _as_f64_dev(t, dtype):
     return t.to(torch.float64)
 
 
-@pytest.mark.parametrize("name", ["cfg1", "cfg2", "cfg3", "cfg4", "cfg4b"])
-def test_full_size(name):
+# every workload on the path the library takes by itself; the two extremes of the single-launch kernels
+# (few huge planes, many tiny ones) also on the multi-sweep kernels a shape falls back to
+@pytest.mark.parametrize("name,fused", [("cfg1", 1), ("cfg2", 1), ("cfg3", 1), ("cfg4", 1), ("cfg4b", 1),
+                                        ("cfg1", 0), ("cfg3", 0)],
+                         ids=["cfg1", "cfg2", "cfg3", "cfg4", "cfg4b", "cfg1-sweeps", "cfg3-sweeps"])
+def test_full_size(name, fused):
+    from paper_1711_07240_amd import cgbn as L
+    old = L.cgbn_get_tuning("fused")
+    L.cgbn_set_tuning("fused", fused)
+    try:
+        _full_size(name, fused)
+    finally:
+        L.cgbn_set_tuning("fused", old)
+
+
+def _full_size(name, fused):
+    from paper_1711_07240_amd import cgbn as L
     wl = synth.WORKLOADS[name]
     t0 = time.time()
     print(f"[case] {name}: generating {wl.S} elements x2 on the host", flush=True)
@@ -39,7 +54,9 @@ def test_full_size(name):
     p.forward()
     p.backward()
     torch.cuda.synchronize()
-    print(f"[case] {name}: kernels done", flush=True)
+    single = (L.cgbn_get_tuning("last_forward_fused"), L.cgbn_get_tuning("last_backward_fused"))
+    assert single == ((1, 1) if fused and wl.layout == "NCHW" else (0, 0)), single
+    print(f"[case] {name}: kernels done (single launch: {single})", flush=True)
 
     # ---- every channel, every element, against the oracle -----------------
     t0 = time.time()
@@ -110,11 +127,22 @@ def test_full_size(name):
     print(f"[ok] {name}: all {wl.C} channels pass the property and library checks", flush=True)
 
 
-@pytest.mark.parametrize("layout", ["NCHW", "NHWC"])
-def test_more_than_2_to_31_elements(layout):
-    """A tensor of 2.36e9 elements (9.4 GB per tensor): 64-bit indexing end to end.  Drawn on the device; the
-    first, a middle and the last channel element by element against the oracle, the last one holding the
-    elements with the highest addresses."""
+@pytest.mark.parametrize("layout,fused", [("NCHW", 1), ("NCHW", 0), ("NHWC", 1)], ids=["NCHW", "NCHW-sweeps", "NHWC"])
+def test_more_than_2_to_31_elements(layout, fused):
+    """A tensor of 2.36e9 elements (9.4 GB per tensor): 64-bit indexing end to end, on the single-launch kernels
+    and on the multi-sweep ones.  Drawn on the device; the first, a middle and the last channel element by
+    element against the oracle, the last one holding the elements with the highest addresses."""
+    from oracle import cgbn_oracle as O
+    from paper_1711_07240_amd import cgbn as L
+    old = L.cgbn_get_tuning("fused")
+    L.cgbn_set_tuning("fused", fused)
+    try:
+        _more_than_2_to_31(layout, fused)
+    finally:
+        L.cgbn_set_tuning("fused", old)
+
+
+def _more_than_2_to_31(layout, fused):
     from oracle import cgbn_oracle as O
     from paper_1711_07240_amd import cgbn as L
     N, C, H, W, K, eps = 32, 128, 512, 1125, 8, 1e-5
@@ -138,6 +166,7 @@ def test_more_than_2_to_31_elements(layout):
     L.cgbn_forward(x, N, C, H, W, layout, K, gamma, beta, eps, y, mean, invstd, "f32", mean_lo, ws)
     L.cgbn_backward(dy, x, mean, invstd, gamma, dx, dgamma, dbeta, N, C, H, W, layout, K, "f32", mean_lo, ws)
     torch.cuda.synchronize()
+    assert L.cgbn_get_tuning("last_forward_fused") == (1 if fused and layout == "NCHW" else 0)
     err = ws[L.cgbn_workspace_error_offset(N, C, H, W, layout, "f32", K):][:4].view(torch.int32)
     assert int(err.item()) == 0
     for c in (0, C // 2 + 1, C - 1):

@@ -61,6 +61,50 @@ def test_one_sweep_forward_then_backward(name, base, kw):
     print(f"[ok] one-sweep {name}: {G.check_against_oracle(got, ref, wl.dtype, name)}", flush=True)
 
 
+@pytest.mark.parametrize("layout", ["NCHW", "NHWC"])
+@pytest.mark.parametrize("sigmas", [5.0, 50.0])
+def test_first_value_far_from_the_mean_is_right_or_flagged(layout, sigmas):
+    """The variant's weak spot: the pivot is the channel's first stored value.  With that value 5 standard
+    deviations off the result must still be right; 50 off, the float rows of (x-p)^2 cannot carry the variance
+    any more, and the call must either still be within tolerance or say so (error word up, NaN statistics for
+    the channel) -- never a silently wrong or clamped variance."""
+    wl = dataclasses.replace(BASE, name=f"far-{sigmas}", N=8, C=8, H=24, W=36, K=4, layout=layout, dtype="f32")
+    d = synth.make_inputs(wl)
+    x = d["x"].copy()
+    for c in (1, 6):                                        # two of the channels get the outlier first value
+        ch = x[:, c] if layout == "NCHW" else x[..., c]
+        first = (0, 0, 0)
+        ch[first] = np.float32(ch.mean() + sigmas * ch.std())
+    p = G.Problem(x, d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
+    flag = torch.zeros(1, dtype=torch.int32, device=G.DEV)
+    p.forward()
+    L.cgbn_workspace_status(p.ws, flag)
+    got = p.results()
+    y, mean, invstd = S.cgbn_forward_one_sweep(x.astype(np.float64), wl.K, d["gamma"].astype(np.float64),
+                                               d["beta"].astype(np.float64), wl.eps, wl.layout)
+    bad = np.isnan(got["invstd"])
+    assert bool(bad.any()) == bool(int(flag.item()))        # the word is up exactly when some channel was refused
+    assert not bad[[0, 2, 3, 4, 5, 7]].any()                # channels with an ordinary first value are never refused
+    if sigmas <= 5.0:
+        assert not bad.any()
+    ok = ~bad
+    assert G.max_rel_err(got["invstd"][ok], invstd[ok], G.rms(invstd[ok])) <= 1e-4
+    assert G.max_rel_err(got["mean"][ok], mean[ok], np.maximum(G.rms(mean[ok]), 1.0 / invstd[ok])) <= 1e-4
+    gy = got["y"][:, ok] if layout == "NCHW" else got["y"][..., ok]
+    ry = y[:, ok] if layout == "NCHW" else y[..., ok]
+    assert float(np.max(np.abs(gy - ry))) <= 1e-4
+    by = got["y"][:, bad] if layout == "NCHW" else got["y"][..., bad]
+    assert np.isnan(by).all()                               # a refused channel's output is NaN throughout
+    # the two-pass path has no such weak spot
+    L.cgbn_set_tuning("one_sweep_stats", 0)
+    flag.zero_()
+    p.forward()
+    L.cgbn_workspace_status(p.ws, flag)
+    got = p.results()
+    assert int(flag.item()) == 0
+    assert G.max_rel_err(got["invstd"], invstd, G.rms(invstd)) <= 1e-4 and float(np.max(np.abs(got["y"] - y))) <= 1e-4
+
+
 def test_matches_the_two_pass_path_closely():
     """Both paths on the same data: statistics agree to a few float roundings."""
     wl = dataclasses.replace(BASE, name="both", N=4, C=64, H=31, W=33, K=2, layout="NHWC")
@@ -89,13 +133,38 @@ def test_relu_variant_uses_it_too():
 
 
 def test_full_size_cfg4():
-    """cfg4's shape, the one this variant is for: every channel's statistics against float64 library reductions."""
+    """cfg4's shape, the one this variant is for: every element of y and every channel's statistics against the
+    one-sweep oracle (per-shard summaries merged pairwise), channel chunk by channel chunk on host threads;
+    every channel's statistics also against float64 library reductions on the device."""
+    from concurrent.futures import ThreadPoolExecutor
     wl = synth.WORKLOADS["cfg4"]
     print("[case] one-sweep cfg4 full size", flush=True)
     d = synth.make_inputs(wl, threads=16)
     p = G.Problem(d["x"], d["dy"], d["gamma"], d["beta"], wl.eps, wl.layout, wl.dtype, wl.K)
     p.forward()
     torch.cuda.synchronize()
+    assert L.cgbn_get_tuning("last_forward_fused") == 0
+    y_host = p.y.cpu().numpy()
+    mean_host = (p.mean.double() + p.mean_lo.double()).cpu().numpy()
+    invstd_host = p.invstd.cpu().numpy().astype(np.float64)
+    per_chunk = max(1, (8 << 20) // wl.M)
+
+    def compare(c0):
+        cs = slice(c0, min(wl.C, c0 + per_chunk))
+        y, mean, invstd = S.cgbn_forward_one_sweep(G.widen(np.ascontiguousarray(d["x"][..., cs]), wl.dtype), wl.K,
+                                                   d["gamma"][cs].astype(np.float64), d["beta"][cs].astype(np.float64),
+                                                   wl.eps, wl.layout)
+        got_y = O.bf16_bits_to_f64(np.ascontiguousarray(y_host[..., cs]).view(np.uint16))
+        e_y = G.max_rel_err(got_y, y, max(G.rms(y), 1e-30))
+        e_m = G.max_rel_err(mean_host[cs], mean, np.maximum(G.rms(mean), 1.0 / invstd))
+        e_i = G.max_rel_err(invstd_host[cs], invstd, G.rms(invstd))
+        assert e_y <= 2e-2 and e_m <= 2e-2 and e_i <= 2e-2, (c0, e_y, e_m, e_i)
+        return e_y, e_m, e_i
+
+    with ThreadPoolExecutor(max_workers=16) as pool:
+        errs = list(pool.map(compare, range(0, wl.C, per_chunk)))
+    print(f"[ok] one-sweep cfg4: every element of y, worst (y, mean, invstd) = {tuple(max(e[i] for e in errs) for i in range(3))}",
+          flush=True)
     x64 = p.x.view(torch.bfloat16).to(torch.float64)
     mean64 = x64.mean(dim=(0, 1, 2))
     var64 = x64.var(dim=(0, 1, 2), unbiased=False)

@@ -67,9 +67,11 @@ def test_random_shape(i, fused):
         xw, dyw = G.widen(d["x"], wl.dtype), G.widen(d["dy"], wl.dtype)
         g64, b64 = d["gamma"].astype(np.float64), d["beta"].astype(np.float64)
         sum_scale = np.sqrt(wl.M) * G.rms(dyw)      # what a channel's gradient sums amount to when nothing cancels
-        if wl.M >= 8:       # with a handful of values per channel eps << var makes dx ill-conditioned in float
-            ref = O.cgbn_forward_backward_ref(xw, dyw, g64, b64, wl.eps, wl.layout)
-            G.check_against_oracle(got, ref, wl.dtype, f"random {i}", sum_scale=sum_scale)
+        # with a handful of values per channel eps << var makes dx (and only dx) ill-conditioned in float:
+        # (1 - xhat^2) of nearly equal terms; everything else is compared whatever M is
+        skip = () if wl.M >= 8 else ("dx",)
+        ref = O.cgbn_forward_backward_ref(xw, dyw, g64, b64, wl.eps, wl.layout)
+        G.check_against_oracle(got, ref, wl.dtype, f"random {i}", sum_scale=sum_scale, skip=skip)
         # ReLU variant with a shortcut on the same shape
         sc_host = np.random.default_rng(i).standard_normal(d["x"].shape).astype(np.float32)
         if wl.dtype == "bf16":
@@ -84,8 +86,7 @@ def test_random_shape(i, fused):
         y_ref, m_ref, i_ref = R.cgbn_relu_forward_ref(xw, g64, b64, wl.eps, wl.layout, residual=G.widen(sc_host, wl.dtype))
         dx_ref, dg_ref, db_ref, dz_ref = R.cgbn_relu_backward_ref(dyw, ys, xw, m_ref, i_ref, g64, wl.layout)
         assert np.array_equal(G.to_host_f64(dz, wl.dtype), dz_ref)
-        if wl.M >= 8:
-            ref = dict(y=y_ref, mean=m_ref, invstd=i_ref, dx=dx_ref, dgamma=dg_ref, dbeta=db_ref)
-            G.check_against_oracle(got, ref, wl.dtype, f"random {i} relu", sum_scale=sum_scale)
+        ref = dict(y=y_ref, mean=m_ref, invstd=i_ref, dx=dx_ref, dgamma=dg_ref, dbeta=db_ref)
+        G.check_against_oracle(got, ref, wl.dtype, f"random {i} relu", sum_scale=sum_scale, skip=skip)
     finally:
         L.cgbn_set_tuning("fused", old)

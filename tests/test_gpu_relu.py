@@ -9,6 +9,7 @@ import pytest
 import torch
 
 import gpu_harness as G
+from oracle import cgbn_oracle as O
 from oracle import cgbn_relu_oracle as R
 from paper_1711_07240_amd import cgbn as L
 from paper_1711_07240_amd import synth
@@ -114,6 +115,20 @@ def run_relu_case(wl, what, with_shortcut):
     if with_shortcut:
         # bit-exact where it is a selection: dz is dy or 0
         assert np.array_equal(got["dz"], np.where(got["y"] > 0, dyw, 0.0))
+    # The mask itself, against the oracle's OWN output rather than the stored one: wherever the value the ReLU
+    # sees is not within rounding of the kink, the library's y is positive exactly where the oracle's is, and
+    # the gradient it lets through is the one a backward masked by the oracle's own y lets through.
+    pre = O.cgbn_forward_ref(xw, g64, b64, wl.eps, wl.layout)[0]
+    if with_shortcut:
+        pre = pre + G.widen(sc_host, wl.dtype)
+    away = np.abs(pre) > 1e-3
+    assert away.mean() > 0.99
+    assert np.array_equal((got["y"] > 0)[away], (pre > 0)[away])
+    if with_shortcut:
+        assert np.array_equal(got["dz"][away], np.where(pre > 0, dyw, 0.0)[away])
+    dx_own, dg_own, db_own, _ = R.cgbn_relu_backward_ref(dyw, np.maximum(pre, 0.0), xw, mean_ref, invstd_ref, g64, wl.layout)
+    near = float(np.abs(dyw[~away]).sum())            # gradient that elements within rounding of the kink could move
+    assert np.all(np.abs(got["dbeta"] - db_own) <= (1e-4 if wl.dtype == "f32" else 2e-2) * np.maximum(np.abs(db_own), G.rms(db_own)) + near)
     print(f"[ok] relu {what}: {rep}", flush=True)
 
 

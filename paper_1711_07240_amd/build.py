@@ -39,7 +39,8 @@ def _units(obj_dir):
             for act in ((0, 1, 2) if fwd else (0, 1)):       # forward: plain, ReLU, shortcut + ReLU
                 obj = os.path.join(OBJ, f"fused_{tname}_{'fwd' if fwd else 'bwd'}_act{act}.o")
                 units.append((obj, os.path.join(CSRC, "cgbn_fused_inst.hip"),
-                              [f"-DCGBN_INST_T={t}", f"-DCGBN_INST_FWD={fwd}", f"-DCGBN_INST_ACT={act}"]))
+                              [f"-DCGBN_INST_T={t}", f"-DCGBN_INST_F32={int(t == 'float')}", f"-DCGBN_INST_FWD={fwd}",
+                               f"-DCGBN_INST_ACT={act}"]))
     return units
 
 

@@ -11,6 +11,7 @@
 #include <cstring>
 #include <map>
 #include <mutex>
+#include <type_traits>
 #include <utility>
 
 // The NCHW single-launch kernels are instantiated in cgbn_fused_inst.hip (one translation
@@ -586,6 +587,21 @@ cgbn_status launch_fused_kernel(KernelT kernel, const Tuning& T, const FusedPlan
     return launched();
 }
 
+// Which (bytes per access, slots per plane) variants exist for an element type, direction and activation: all of
+// the list header's, except that the float ReLU backward is not built with 4-byte accesses (one slot count
+// excepted; see CGBN_FUSED_RELU_BWD_F32_NARROW).  A shape whose variant is not built takes the multi-sweep kernels.
+template <typename T, bool FWD, int ACT> constexpr bool fused_built(int LB, int LPPC)
+{
+    if (std::is_same<T, float>::value && !FWD && ACT == 1 && LB == 4) {
+        bool built = false;
+#define CGBN_IS_BUILT(LB_, LPPC_) built = built || (LB == LB_ && LPPC == LPPC_);
+        CGBN_FUSED_RELU_BWD_F32_NARROW(CGBN_IS_BUILT)
+#undef CGBN_IS_BUILT
+        return built;
+    }
+    return true;
+}
+
 // ACT: 0 plain, 1 ReLU, 2 shortcut + ReLU (forward only)
 template <typename T, bool FWD, int ACT>
 cgbn_status launch_fused_t(const Tuning& knobs, const FusedPlan& f, FusedArgs& A, int sync_words, hipStream_t st, bool* taken,
@@ -601,6 +617,7 @@ cgbn_status launch_fused_t(const Tuning& knobs, const FusedPlan& f, FusedArgs& A
         else return launch_fused_kernel(nchw_fused_backward<T, 16, -2, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes);
     }
 #define CGBN_FUSED_CASE2(LB_, LPPC_)                                                                         \
+    if constexpr (fused_built<T, FWD, ACT>(LB_, LPPC_))                                                      \
     if (f.big == 2 && f.LB == LB_ && f.LPPC == LPPC_) {                                                      \
         if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 2>, knobs, f, A, sync_words, st, taken, moved_bytes); \
         else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 2>, knobs, f, A, sync_words, st, taken, moved_bytes); \
@@ -608,6 +625,7 @@ cgbn_status launch_fused_t(const Tuning& knobs, const FusedPlan& f, FusedArgs& A
     CGBN_FUSED_BIG_SMALL(CGBN_FUSED_CASE2)
 #undef CGBN_FUSED_CASE2
 #define CGBN_FUSED_CASE(LB_, LPPC_)                                                                          \
+    if constexpr (fused_built<T, FWD, ACT>(LB_, LPPC_))                                                      \
     if (f.LB == LB_ && f.LPPC == LPPC_) {                                                                    \
         if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 0>, knobs, f, A, sync_words, st, taken, moved_bytes); \
         else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 0>, knobs, f, A, sync_words, st, taken, moved_bytes); \

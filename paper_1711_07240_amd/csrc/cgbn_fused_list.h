@@ -6,17 +6,28 @@
 // tile each per workgroup.  X(LB, LPPC).
 #pragma once
 
-#define CGBN_FUSED_COMMON(X)                                                                  \
+#define CGBN_FUSED_COMMON_WIDE(X)                                                             \
     X(16, 0) X(8, 0) X(16, -2)                                                                \
     X(16, 2) X(16, 3) X(16, 4) X(16, 5) X(16, 6) X(16, 8) X(16, 10) X(16, 12) X(16, 16)       \
-    X(8, 4) X(8, 5) X(8, 6) X(8, 8) X(8, 10) X(8, 12) X(8, 16) X(8, 24) X(8, 32)                \
-    X(4, 8) X(4, 10) X(4, 12) X(4, 16) X(4, 24) X(4, 32) X(4, 64)
+    X(8, 4) X(8, 5) X(8, 6) X(8, 8) X(8, 10) X(8, 12) X(8, 16) X(8, 24) X(8, 32)
+#define CGBN_FUSED_COMMON_NARROW(X) X(4, 8) X(4, 10) X(4, 12) X(4, 16) X(4, 24) X(4, 32) X(4, 64)
+#define CGBN_FUSED_COMMON(X) CGBN_FUSED_COMMON_WIDE(X) CGBN_FUSED_COMMON_NARROW(X)
 // The last two of each line: planes up to 6 KiB (forward) / 3 KiB (backward, per tensor) longer than a wavefront's
 // share of the registers: one plane per wavefront, the slots beyond the registers in LDS.
 #define CGBN_FUSED_FORWARD_ONLY(X) X(16, 24) X(16, 32) X(8, 64) X(4, 128) X(16, 38) X(8, 76)
-#define CGBN_FUSED_BACKWARD_ONLY(X) X(8, 2) X(8, 3) X(4, 4) X(4, 5) X(4, 6) X(16, 19) X(8, 38)
+#define CGBN_FUSED_BACKWARD_ONLY_WIDE(X) X(8, 2) X(8, 3) X(16, 19) X(8, 38)
+#define CGBN_FUSED_BACKWARD_ONLY_NARROW(X) X(4, 4) X(4, 5) X(4, 6)
+#define CGBN_FUSED_BACKWARD_ONLY(X) CGBN_FUSED_BACKWARD_ONLY_WIDE(X) CGBN_FUSED_BACKWARD_ONLY_NARROW(X)
 
 // Small planes with few rows and shards to stage (BIG == 2): further whole planes per wavefront in LDS.
 // Only slot counts for which at least one plane fits the LDS share of either direction.
-#define CGBN_FUSED_BIG_SMALL(X)                                                               \
-    X(4, 8) X(4, 10) X(4, 12) X(4, 16) X(8, 4) X(8, 5) X(8, 6) X(8, 8) X(8, 10) X(16, 2) X(16, 3) X(16, 4) X(16, 5)
+#define CGBN_FUSED_BIG_SMALL_WIDE(X) X(8, 4) X(8, 5) X(8, 6) X(8, 8) X(8, 10) X(16, 2) X(16, 3) X(16, 4) X(16, 5)
+#define CGBN_FUSED_BIG_SMALL_NARROW(X) X(4, 8) X(4, 10) X(4, 12) X(4, 16)
+#define CGBN_FUSED_BIG_SMALL(X) CGBN_FUSED_BIG_SMALL_WIDE(X) CGBN_FUSED_BIG_SMALL_NARROW(X)
+
+// The ReLU backward of float tensors is not built with 4-byte accesses, one slot count excepted: next to the stored
+// output's extra round of loads those variants do not fit a wavefront's register budget (65 to 104 registers go
+// to scratch memory) and run slower than the multi-sweep kernels (measured, 64 x 1024 channels: planes of 255
+// to 4095 floats 1.3 to 1.6 times slower; the 24-slot variant, planes of 1075 to 1535 floats, 1.5 times faster).
+// Such shapes take the multi-sweep kernels for that call.
+#define CGBN_FUSED_RELU_BWD_F32_NARROW(X) X(4, 24)

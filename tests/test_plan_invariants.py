@@ -19,14 +19,20 @@ BIG_ROWS, BIG_SHARDS_LARGE, BIG_SHARDS_SMALL = 384, 48, 128
 
 
 def _built():
-    """(LB, LPPC) pairs the single-launch kernels are instantiated for, from the list header."""
+    """(LB, LPPC) pairs the single-launch kernels are instantiated for, from the list header (a list may be
+    made of other lists)."""
     text = open(os.path.join(ROOT, "paper_1711_07240_amd", "csrc", "cgbn_fused_list.h")).read()
     text = text.replace("\\\n", " ")
-    out = {}
-    for name in ("COMMON", "FORWARD_ONLY", "BACKWARD_ONLY", "BIG_SMALL"):
-        m = re.search(r"#define CGBN_FUSED_%s\(X\)(.*)" % name, text)
-        out[name] = {(int(a), int(b)) for a, b in re.findall(r"X\((\d+),\s*(-?\d+)\)", m.group(1))}
-    return out
+    bodies = dict(re.findall(r"#define CGBN_FUSED_(\w+)\(X\)(.*)", text))
+
+    def pairs(name):
+        body = bodies[name]
+        out = {(int(a), int(b)) for a, b in re.findall(r"\bX\((\d+),\s*(-?\d+)\)", body)}
+        for sub in re.findall(r"CGBN_FUSED_(\w+)\(X\)", body):
+            out |= pairs(sub)
+        return out
+
+    return {name: pairs(name) for name in ("COMMON", "FORWARD_ONLY", "BACKWARD_ONLY", "BIG_SMALL", "RELU_BWD_F32_NARROW")}
 
 
 BUILT = _built()

@@ -166,8 +166,10 @@ def measure_workload(layer, torch, steps, warmup):
     fwd_in, bwd_in = time_step_halves(torch, layer, steps)
     per_step = [f + b for f, b in zip(fwd_in, bwd_in)]
     fused_f, fused_b = (layer.cgbn.cgbn_get_tuning("last_forward_fused"), layer.cgbn.cgbn_get_tuning("last_backward_fused"))
-    # bytes the step moves by design: 5 tensors when both directions run as one launch each, 9 as separate sweeps
-    moved = ((2 if fused_f else 4) + (3 if fused_b else 5)) * Sb
+    # bytes the step moves by design: 5 tensors when both directions run as one launch each; as separate sweeps
+    # the forward moves 3 (statistics from one sweep over x, the default) or 4, the backward 5
+    one_sweep = layer.cgbn.cgbn_get_tuning("one_sweep_stats")
+    moved = ((2 if fused_f else (3 if one_sweep else 4)) + (3 if fused_b else 5)) * Sb
     return dict(
         workload=wl.name, ms_per_step=wall_ms, fwd_ms=statistics.median(fwd_in), bwd_ms=statistics.median(bwd_in),
         bwd_ms_mean=statistics.mean(bwd_in),
@@ -365,17 +367,15 @@ def main():
         l2 = Layer(w2, torch, cgbn, *device_inputs_fast(w2, torch, synth, dev))
         others.append(measure_workload(l2, torch, max(5, args.steps // 5), max(2, args.warmup // 2)))
         if not others[-1]["single_launch"]["forward"]:
-            # the forward runs as separate sweeps: also with the one-sweep statistics variant (not Algorithm 1's
-            # two passes; 7 instead of 9 tensor sweeps per step, priced on its own byte count)
-            cgbn.cgbn_set_tuning("one_sweep_stats", 1)
-            v = measure_workload(l2, torch, max(5, args.steps // 5), 2)
+            # the forward runs as separate sweeps: also with a sweep each for the sums and the squared deviations
+            # (9 instead of 8 tensor sweeps per step)
             cgbn.cgbn_set_tuning("one_sweep_stats", 0)
-            Sb2 = w2.S * w2.elem_bytes
-            others[-1]["one_sweep_stats_variant"] = dict(
-                ms_per_step=v["ms_per_step"], fwd_ms=v["fwd_ms"], moved_bytes_by_design=7 * Sb2,
-                moved_GBps=7 * Sb2 / v["ms_per_step"] / 1e6,
-                pct_of_peak_on_moved_bytes=7 * Sb2 / v["ms_per_step"] / 1e6 / PEAK_GBPS * 100,
-                pct_of_peak_on_min_bytes=5 * Sb2 / v["ms_per_step"] / 1e6 / PEAK_GBPS * 100)
+            v = measure_workload(l2, torch, max(5, args.steps // 5), 2)
+            cgbn.cgbn_set_tuning("one_sweep_stats", 1)
+            others[-1]["two_sweep_statistics"] = dict(
+                ms_per_step=v["ms_per_step"], fwd_ms=v["fwd_ms"], moved_bytes_by_design=v["moved_bytes_by_design"],
+                moved_GBps=v["moved_GBps"], pct_of_peak_on_moved_bytes=v["pct_of_peak_on_moved_bytes"],
+                pct_of_peak_on_min_bytes=v["pct_of_peak_on_min_bytes"])
         if w2.S * w2.elem_bytes <= (1 << 20):
             # launch-latency bound (the tensors live in L2): also as a replayed HIP graph
             others[-1]["ms_per_step_graph_replay"] = measure_graph(l2, torch, 200)

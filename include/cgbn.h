@@ -268,12 +268,13 @@ const char* cgbn_status_string(cgbn_status status);
  *   "reverse"          0/1: alternate the sweep direction between consecutive sweeps
  *   "nt_store"         0/1: non-temporal stores for y and dx
  *   "fused"            0/1: register-resident single-launch forward/backward (NCHW)
- *   "one_sweep_stats"  0/1 (default 0): where cgbn_forward runs as separate sweeps, take the statistics in ONE
- *                      sweep -- per-shard (count, mean, M2) about a per-channel pivot (the channel's first value),
- *                      merged pairwise -- instead of Algorithm 1's two; same results up to rounding, 3 tensor
- *                      sweeps instead of 4.  Accurate while the pivot lies within about eleven standard deviations
- *                      of the channel's mean; a channel where it does not gets NaN statistics and the workspace's
- *                      error word is raised (cgbn_workspace_status), never a variance of unknown accuracy
+ *   "one_sweep_stats"  0/1 (default 1): where cgbn_forward runs as separate sweeps, steps 1-10 come from ONE sweep
+ *                      over x: each row partial is the sum about a per-channel pivot and M2, the squared
+ *                      deviations from the row's own mean (formed chunk by chunk in registers, never as a
+ *                      difference of large sums); the combine step turns them into Algorithm 1's sums about the
+ *                      pooled mean by the pairwise update.  3 tensor sweeps instead of 4, same results up to
+ *                      rounding.  0: one sweep for the sums, a second for the squared deviations (what the
+ *                      step-by-step entry points below always do)
  *   "cooperative"      0/1 (default 0): launch the single-launch kernels cooperatively, so that the runtime
  *                      guarantees the whole grid is resident; needed only if such calls can overlap on
  *                      different streams; costs about 15 us per launch

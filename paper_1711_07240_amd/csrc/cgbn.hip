@@ -95,7 +95,7 @@ struct Tuning {
     long long spin_limit = 1LL << 24;    // polls of a bounded wait in the fused kernels before it gives up
     long long cooperative = 0;           // launch the single-launch kernels cooperatively (co-residency guaranteed by the runtime)
     long long big_lds = 1;               // large planes with few rows/shards: keep more unit data in LDS
-    long long one_sweep_stats = 0;       // forward statistics in one sweep (a variant, not Algorithm 1's two passes)
+    long long one_sweep_stats = 1;       // multi-sweep forward: steps 1-10 from one sweep over x (0: a sweep for the sums, one for the deviations)
     long long fused_groups = 0;          // workgroups of the fused grid (0 = as many as are resident at once)
     long long stagger = 1;               // single-launch kernels: start the channel slots class by class (see choose_stagger)
     long long stagger_us = 0;            // ... start-up delay of the last class (0 = chosen per launch)
@@ -490,10 +490,9 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
     A.C = p.C; A.rows = p.rows; A.K = p.K; A.rps = p.rps; A.G = p.G;
     if (p.layout == CGBN_NCHW) { A.cs = p.rows; A.rs = 1; } else { A.cs = 1; A.rs = p.C; }
     A.clear_word = reinterpret_cast<unsigned*>(ws + p.off_sync) + 1;
-    if (mode == CM_MOMENTS) {       // this mode may raise the word: the sweep before it has cleared it
-        A.raise_word = A.clear_word;
-        A.clear_word = nullptr;
-    }
+    // values per row partial: a chunk of a plane (the last chunk shorter), a whole plane, or a pixel run of a shard
+    if (p.layout == CGBN_NCHW) { A.row_mod = p.sp; A.row_full = p.wave_mode ? p.HW : p.L; A.row_total = p.HW; }
+    else { A.row_mod = p.pps; A.row_full = p.PL; A.row_total = p.spix; }
     dim3 grid((unsigned)((p.C + 3) / 4)), block(kThreads);
     switch (mode) {
     case CM_MEAN:   hipLaunchKernelGGL((combine_rows<CM_MEAN>), grid, block, 0, st, A); break;
@@ -896,12 +895,12 @@ cgbn_status forward_impl(const Tuning& T, const void* x, const void* shortcut, b
     SweepArgs A = sweep_args(p);
     A.x = x; A.part0 = part0;
     if (p.t.one_sweep_stats) {
-        // Not Algorithm 1: one sweep leaves every shard's (count, mean, M2), merged pairwise into the
-        // pooled statistics; then step 11 as usual.  3 sweeps of the tensor instead of 4.
+        // Steps 1-10 from ONE sweep over x: every row partial is (sum about the pivot, M2 about the row's own
+        // mean); the combine step adds the sums (steps 4-5) and turns the M2s into the squared deviations from
+        // the pooled mean by the pairwise update M2 + M2' + (mean' - mean)^2 n n'/(n + n') (steps 6-10: the same
+        // number, term for term, as summing (x - mean)^2 directly).  Then step 11: 3 sweeps of the tensor instead of 4.
         A.part1 = reinterpret_cast<float*>(ws + p.off_part1);
-        A.clear_word = reinterpret_cast<unsigned*>(ws + p.off_sync) + 1;
         CGBN_TRY(launch_reduce(OP_MOMENTS, p, A, st));
-        A.clear_word = nullptr;
         CGBN_TRY(launch_combine(CM_MOMENTS, p, ws, mean, mlo, mean_lo, nullptr, nullptr, (double)eps, x, st, invstd));
         A.mean = mean; A.mean_lo = mlo; A.invstd = invstd; A.gamma = gamma; A.beta = beta; A.out = y;
         A.reverse = rev; A.dy = shortcut;

@@ -14,8 +14,8 @@
 //   map     EL_DX_RELU        dx from dz; optionally writes dz, the shortcut's gradient
 //   map     EL_FROZEN         y  = gamma*(x-m)/sqrt(s2+eps) + beta with fixed statistics m, s2 (sections 3.1, 3.3)
 //   map     EL_SCALE          dx = dy*gamma/sqrt(s2+eps), the backward of the fixed-statistics layer
-//   reduce  OP_MOMENTS        sum (x - p), sum (x - p)^2 about the channel's pivot p: the one-sweep
-//                             statistics variant (not Algorithm 1's two passes)
+//   reduce  OP_MOMENTS        per row, sum (x - p) about the channel's pivot p and M2, the squared deviations from the
+//                             row's OWN mean: steps 1-3 and the raw material of steps 6-8 in one sweep over x
 // A reduce sweep leaves one float per (channel, row) in `part`, where the rows
 // of a channel are ordered shard by shard; combine_rows then adds the rows of a
 // shard (the device sum of Algorithm 1) and the shards (its reduce step) in
@@ -74,8 +74,6 @@ struct SweepArgs {
     float eps;                // fixed-statistics maps: `invstd` then points at variances
     int reverse;              // walk the grid backwards
     int nt;                   // non-temporal stores
-    unsigned* clear_word;     // reductions: set to zero if not null (the workspace's error word, where a later
-                              // kernel of the same call may raise it)
 };
 
 // --------------------------------------------------------------------------
@@ -181,6 +179,63 @@ template <int V> __device__ __forceinline__ float fold(const float (&a)[V])
 }
 
 // --------------------------------------------------------------------------
+// one-sweep statistics: running summaries (count, sum, M2)
+// --------------------------------------------------------------------------
+
+// A summary of a set of values taken about the channel's pivot: how many, their sum, and M2, the sum of their
+// squared deviations from the set's OWN mean.  Values arrive in small chunks whose sum and M2 are formed exactly
+// as written (sum, mean, deviations from that mean: everything is in registers); a chunk is merged into the
+// running summary by the pairwise update
+//     M2 <- M2 + M2_chunk + (mean_chunk - mean)^2 * n * c / (n + c)
+// so nothing is ever formed as a difference of large sums, wherever the pivot lies.
+struct Run {
+    float n, S, M2;
+};
+// merge of two summaries (a to the left of b: the order is part of the result's bits)
+__device__ __forceinline__ Run run_join(const Run& a, const Run& b)
+{
+    const float n = a.n + b.n;
+    const float ma = a.n > 0.f ? a.S * __builtin_amdgcn_rcpf(a.n) : 0.f;
+    const float mb = b.n > 0.f ? b.S * __builtin_amdgcn_rcpf(b.n) : 0.f;
+    const float w = n > 0.f ? a.n * b.n * __builtin_amdgcn_rcpf(n) : 0.f;
+    const float d = mb - ma;
+    Run r;
+    r.n = n;
+    r.S = a.S + b.S;
+    r.M2 = (a.M2 + b.M2) + (d * d) * w;
+    return r;
+}
+// a chunk of C values v[] (already taken about the pivot) joins the summary
+template <int C> __device__ __forceinline__ void run_feed(Run& r, const float (&v)[C])
+{
+    float cs = 0.f;
+#pragma unroll
+    for (int i = 0; i < C; ++i) cs += v[i];
+    const float cm = cs * (1.0f / (float)C);
+    float cq = 0.f;
+#pragma unroll
+    for (int i = 0; i < C; ++i) {
+        const float d = v[i] - cm;
+        cq += d * d;
+    }
+    Run c = {(float)C, cs, cq};
+    r = run_join(r, c);
+}
+// all 64 lanes' summaries joined in a fixed tree (the lower lane always on the left); every lane gets the result
+__device__ __forceinline__ Run run_wave_join(Run mine, int lane)
+{
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        Run other;
+        other.n = __shfl_xor(mine.n, off);
+        other.S = __shfl_xor(mine.S, off);
+        other.M2 = __shfl_xor(mine.M2, off);
+        mine = (lane & off) ? run_join(other, mine) : run_join(mine, other);
+    }
+    return mine;
+}
+
+// --------------------------------------------------------------------------
 // walking one contiguous run of elements with 16-byte vector accesses
 // --------------------------------------------------------------------------
 
@@ -261,10 +316,6 @@ template <int OP> __device__ __forceinline__ void accumulate(const ChanConst& k,
     if (op_has_y(OP)) dyv = yv > 0.f ? dyv : 0.f;
     if (OP == OP_SUM) {
         a0 += xv - k.mu;
-    } else if (OP == OP_MOMENTS) {
-        float d = xv - k.mu;
-        a0 += d;
-        a1 += d * d;
     } else if (OP == OP_SQDEV) {
         float d = (xv - k.mu) - k.mulo;
         a0 += d * d;
@@ -307,9 +358,15 @@ template <typename T, int OP> struct PlaneReduce {
     const T* aux;
     ChanConst k;
     float a0[VEC], a1[VEC];
+    Run run;                       // OP_MOMENTS: this lane's summary
 
     __device__ __forceinline__ void one(long long off)
     {
+        if constexpr (OP == OP_MOMENTS) {
+            float v[1] = {Elem<T>::load1(x + off) - k.mu};
+            run_feed<1>(run, v);
+            return;
+        }
         float xv = Elem<T>::load1(x + off);
         float dv = DY ? Elem<T>::load1(dy + off) : 0.f;
         float yv = Y ? Elem<T>::load1(aux + off) : 0.f;
@@ -319,6 +376,12 @@ template <typename T, int OP> struct PlaneReduce {
     {
         float xv[VEC], dv[VEC], yv[VEC];
         Elem<T>::loadv(x + off, xv);
+        if constexpr (OP == OP_MOMENTS) {
+#pragma unroll
+            for (int e = 0; e < VEC; ++e) xv[e] -= k.mu;
+            run_feed<VEC>(run, xv);
+            return;
+        }
         if (DY) Elem<T>::loadv(dy + off, dv);
         if (Y) Elem<T>::loadv(aux + off, yv);
 #pragma unroll
@@ -329,6 +392,15 @@ template <typename T, int OP> struct PlaneReduce {
         float xv[4][VEC], dv[4][VEC], yv[4][VEC];
 #pragma unroll
         for (int u = 0; u < 4; ++u) Elem<T>::loadv(x + off + u * step, xv[u]);
+        if constexpr (OP == OP_MOMENTS) {
+            float v[4 * VEC];              // one chunk: all of them are values of this plane
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) v[u * VEC + e] = xv[u][e] - k.mu;
+            run_feed<4 * VEC>(run, v);
+            return;
+        }
         if (DY) {
 #pragma unroll
             for (int u = 0; u < 4; ++u) Elem<T>::loadv(dy + off + u * step, dv[u]);
@@ -413,7 +485,6 @@ __global__ __launch_bounds__(kThreads) void nchw_reduce_block(SweepArgs A)
     constexpr int VEC = Elem<T>::VEC;
     constexpr int Q = op_sums(OP);
     __shared__ float sm[2 * 4];
-    if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int j = (int)(b % A.sp);
     long long plane = b / A.sp;
@@ -429,10 +500,25 @@ __global__ __launch_bounds__(kThreads) void nchw_reduce_block(SweepArgs A)
     f.k = reduce_consts<T, OP>(A, c);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { f.a0[e] = 0.f; f.a1[e] = 0.f; }
+    f.run = Run{0.f, 0.f, 0.f};
     walk_segment<kThreads, VEC>(plane * A.HW + beg, len, (int)threadIdx.x, A.S, f);
 
-    float v[2] = {wave_sum(fold<VEC>(f.a0)), Q == 2 ? wave_sum(fold<VEC>(f.a1)) : 0.f};
     int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
+    if constexpr (OP == OP_MOMENTS) {
+        // the lanes' summaries, then the four wavefronts', joined in a fixed order: the row is (sum, M2)
+        __shared__ Run wr[4];
+        const Run r = run_wave_join(f.run, lane);
+        if (lane == 0) wr[w] = r;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const Run t = run_join(run_join(wr[0], wr[1]), run_join(wr[2], wr[3]));
+            size_t o = (size_t)c * A.rows + (size_t)n * A.sp + j;
+            A.part0[o] = t.S;
+            A.part1[o] = t.M2;
+        }
+        return;
+    }
+    float v[2] = {wave_sum(fold<VEC>(f.a0)), Q == 2 ? wave_sum(fold<VEC>(f.a1)) : 0.f};
     if (lane == 0) { sm[w] = v[0]; sm[4 + w] = v[1]; }
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -448,7 +534,6 @@ __global__ __launch_bounds__(kThreads) void nchw_reduce_wave(SweepArgs A)
 {
     constexpr int VEC = Elem<T>::VEC;
     constexpr int Q = op_sums(OP);
-    if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int lane = threadIdx.x & (kWave - 1), w = threadIdx.x >> 6;
     long long plane = b * 4 + w;
@@ -463,8 +548,18 @@ __global__ __launch_bounds__(kThreads) void nchw_reduce_wave(SweepArgs A)
     f.k = reduce_consts<T, OP>(A, c);
 #pragma unroll
     for (int e = 0; e < VEC; ++e) { f.a0[e] = 0.f; f.a1[e] = 0.f; }
+    f.run = Run{0.f, 0.f, 0.f};
     walk_segment<kWave, VEC>(plane * A.HW, A.HW, lane, A.S, f);
 
+    if constexpr (OP == OP_MOMENTS) {
+        const Run r = run_wave_join(f.run, lane);
+        if (lane == 0) {
+            size_t o = (size_t)c * A.rows + n;
+            A.part0[o] = r.S;
+            A.part1[o] = r.M2;
+        }
+        return;
+    }
     float v0 = wave_sum(fold<VEC>(f.a0));
     float v1 = Q == 2 ? wave_sum(fold<VEC>(f.a1)) : 0.f;
     if (lane == 0) {
@@ -527,7 +622,6 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
 {
     constexpr int Q = op_sums(OP);
     __shared__ float sm[Q * kThreads * V];
-    if (A.clear_word && blockIdx.x == 0 && threadIdx.x == 0) *A.clear_word = 0u;
     long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
     int ct = (int)(b % A.ctiles);
     int row = (int)(b / A.ctiles);
@@ -543,6 +637,7 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
     int cb = vc * V;
 
     float a0[V], a1[V];
+    float cnt = 0.f;                 // OP_MOMENTS: values per channel this thread has taken in so far
 #pragma unroll
     for (int e = 0; e < V; ++e) { a0[e] = 0.f; a1[e] = 0.f; }
     if (active) {
@@ -569,6 +664,32 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
 #pragma unroll
                 for (int u = 0; u < UNR; ++u) Access<T, V>::load(py + (long long)(i + u * rpp) * C, yv[u]);
             }
+            if constexpr (OP == OP_MOMENTS) {
+                // a chunk of UNR pixels joins this thread's summaries (a0: sum, a1: M2); the count and the
+                // weights of the join are the same for all of the thread's channels
+                const float rn = cnt > 0.f ? __builtin_amdgcn_rcpf(cnt) : 0.f;
+                const float wj = cnt * (float)UNR * __builtin_amdgcn_rcpf(cnt + (float)UNR);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    float cs = 0.f, cq = 0.f;
+#pragma unroll
+                    for (int u = 0; u < UNR; ++u) {
+                        xv[u][e] -= kc[e].mu;
+                        cs += xv[u][e];
+                    }
+                    const float cm = cs * (1.0f / (float)UNR);
+#pragma unroll
+                    for (int u = 0; u < UNR; ++u) {
+                        const float d = xv[u][e] - cm;
+                        cq += d * d;
+                    }
+                    const float d = cm - a0[e] * rn;
+                    a1[e] += cq + (d * d) * wj;
+                    a0[e] += cs;
+                }
+                cnt += (float)UNR;
+                continue;
+            }
 #pragma unroll
             for (int u = 0; u < UNR; ++u)
 #pragma unroll
@@ -578,6 +699,19 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
         for (; i < npix; i += rpp) {
             float xv[V], dv[V], yv[V];
             Access<T, V>::load(px + (long long)i * C, xv);
+            if constexpr (OP == OP_MOMENTS) {
+                const float rn = cnt > 0.f ? __builtin_amdgcn_rcpf(cnt) : 0.f;
+                const float wj = cnt * __builtin_amdgcn_rcpf(cnt + 1.f);
+#pragma unroll
+                for (int e = 0; e < V; ++e) {
+                    const float v = xv[e] - kc[e].mu;
+                    const float d = v - a0[e] * rn;
+                    a1[e] += (d * d) * wj;
+                    a0[e] += v;
+                }
+                cnt += 1.f;
+                continue;
+            }
             if (DY) Access<T, V>::load(pd + (long long)i * C, dv);
             if (Y) Access<T, V>::load(py + (long long)i * C, yv);
 #pragma unroll
@@ -598,9 +732,21 @@ __global__ __launch_bounds__(kThreads) void nhwc_reduce(SweepArgs A)
         int ch = ct * nout + o;
         if (ch >= A.C) continue;
         float s0 = 0.f, s1 = 0.f;
-        for (int rr = 0; rr < A.rpp; ++rr) {
-            s0 += sm[(0 * A.rpp + rr) * nout + o];
-            if (Q == 2) s1 += sm[(1 * A.rpp + rr) * nout + o];
+        if constexpr (OP == OP_MOMENTS) {
+            // the pixel rows' summaries joined in row order; row rr took pixels rr, rr + rpp, ... of the piece
+            Run acc = {0.f, 0.f, 0.f};
+            for (int rr = 0; rr < A.rpp; ++rr) {
+                const int n_rr = rr < npix ? (npix - rr + A.rpp - 1) / A.rpp : 0;
+                Run part = {(float)n_rr, sm[(0 * A.rpp + rr) * nout + o], sm[(1 * A.rpp + rr) * nout + o]};
+                acc = run_join(acc, part);
+            }
+            s0 = acc.S;
+            s1 = acc.M2;
+        } else {
+            for (int rr = 0; rr < A.rpp; ++rr) {
+                s0 += sm[(0 * A.rpp + rr) * nout + o];
+                if (Q == 2) s1 += sm[(1 * A.rpp + rr) * nout + o];
+            }
         }
         size_t po = (size_t)row * A.C + ch;          // consecutive threads, consecutive floats: whole lines per store
         A.part0[po] = s0;
@@ -696,9 +842,8 @@ struct CombineArgs {
     long long pivot_stride;
     int is_bf16;
     int C, rows, K, rps, G; // G lanes share one shard, a power of two <= 64
+    long long row_mod, row_full, row_total;   // CM_MOMENTS: values per row (see merge_shard_moments)
     unsigned* clear_word;   // set to zero if not null (the workspace's error word)
-    unsigned* raise_word;   // CM_MOMENTS: set to one when a channel's statistics cannot be vouched for (cleared by
-                            // the sweep before, never by this kernel)
 };
 
 __device__ __forceinline__ double pivot_of(const CombineArgs& A, int c)
@@ -761,44 +906,40 @@ __device__ __forceinline__ Moments merge_moments(const Moments& a, const Moments
     return r;
 }
 
-// Rows of sum(x - p) and sum((x - p)^2) -> one summary per shard (its mean taken about
-// the pivot p) -> all shards merged.  Shards are dealt to lane groups as in
-// shard_then_total; a lane merges its shards in order, then the 64 lanes merge in a
-// fixed tree (the lower lane always on the left).  Double precision throughout.
-// A shard's M2 is formed as sum (x-p)^2 - n * mean^2: sound as long as the pivot lies within a
-// few spreads of the data, because the float rows of (x-p)^2 carry a rounding of about 1e-7
-// of THEIR size.  `raw` returns the channel's total of those rows, so that the caller can tell
-// when that rounding is no longer small against the pooled M2 (nothing is clamped here).
-__device__ __forceinline__ Moments merge_shard_moments(const float* p1, const float* p2, const CombineArgs& A, int lane,
-                                                       double* raw)
+// Rows of (sum(x - p), M2 about the row's own mean) -> one summary per shard (its mean taken
+// about the pivot p) -> all shards merged.  Shards are dealt to lane groups as in
+// shard_then_total; the lanes of a group merge their rows of the shard in order and then among
+// themselves, a lane merges its shards in order, then the 64 lanes merge in a fixed tree (the
+// lower lane always on the left).  Double precision throughout; every M2 that enters is a sum
+// of squares about its own set's mean, so nothing is formed as a difference of large numbers.
+// Row r of a channel holds min(row_full, row_total - (r % row_mod) * row_full) values.
+__device__ __forceinline__ Moments merge_shard_moments(const float* p1, const float* p2, const CombineArgs& A, int lane)
 {
-    double raw_mine = 0.0;
     const int G = A.G;
     const int gl = lane & (G - 1), gi = lane / G, spp = kWave / G;
     Moments mine = {0.0, 0.0, 0.0};
     for (int k0 = 0; k0 < A.K; k0 += spp) {
         const int k = k0 + gi;
-        double s1 = 0.0, s2 = 0.0;
+        Moments sk = {0.0, 0.0, 0.0};
         if (k < A.K)
             for (int r = gl; r < A.rps; r += G) {
-                s1 += (double)p1[((size_t)k * A.rps + r) * A.rs];
-                s2 += (double)p2[((size_t)k * A.rps + r) * A.rs];
+                const long long row = (long long)k * A.rps + r;
+                const long long left = A.row_total - (row % A.row_mod) * A.row_full;
+                Moments m;
+                m.n = (double)(left < A.row_full ? left : A.row_full);
+                m.mean = (double)p1[(size_t)row * A.rs] / m.n;             // about the pivot
+                m.m2 = (double)p2[(size_t)row * A.rs];
+                sk = merge_moments(sk, m);
             }
-        for (int off = G >> 1; off >= 1; off >>= 1) {
-            s1 += __shfl_xor(s1, off);
-            s2 += __shfl_xor(s2, off);
+        for (int off = 1; off < G; off <<= 1) {       // the group's lanes, the lower lane on the left
+            Moments other;
+            other.n = __shfl_xor(sk.n, off);
+            other.mean = __shfl_xor(sk.mean, off);
+            other.m2 = __shfl_xor(sk.m2, off);
+            sk = (gl & off) ? merge_moments(other, sk) : merge_moments(sk, other);
         }
-        if (k < A.K && gl == 0) {
-            Moments sk;
-            sk.n = A.shard_count;
-            sk.mean = s1 / sk.n;                     // about the pivot
-            sk.m2 = s2 - s1 * sk.mean;               // sum (x-p)^2 - n * mean^2
-            raw_mine += s2;
-            mine = merge_moments(mine, sk);
-        }
+        if (k < A.K && gl == 0) mine = merge_moments(mine, sk);
     }
-    for (int off = kWave >> 1; off >= 1; off >>= 1) raw_mine += __shfl_xor(raw_mine, off);
-    *raw = raw_mine;
     for (int off = 1; off < kWave; off <<= 1) {
         Moments other;
         other.n = __shfl_xor(mine.n, off);
@@ -818,21 +959,12 @@ __global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
     if (c >= A.C) return;
     const double pivot = pivot_of(A, c);      // zero unless the rows hold sums about a pivot
     if (MODE == CM_MOMENTS) {
-        double raw = 0.0;
-        Moments m = merge_shard_moments(A.part0 + (size_t)c * A.cs, A.part1 + (size_t)c * A.cs, A, lane, &raw);
+        Moments m = merge_shard_moments(A.part0 + (size_t)c * A.cs, A.part1 + (size_t)c * A.cs, A, lane);
         if (lane != 0) return;
         double mean = pivot + m.mean;
         float hi = (float)mean;
         float lo = (float)(mean - (double)hi);
-        float istd = (float)(1.0 / sqrt((m.m2 > 0.0 ? m.m2 : 0.0) / A.M + A.eps));
-        // raw = M2 + M (mean - p)^2: when the pooled mean lies more than about eleven spreads from the pivot the
-        // rounding of the rows (1e-7 of raw) is no longer small against M2.  Then this one-sweep variant cannot
-        // keep its accuracy: it says so (error word, NaN statistics) instead of returning a variance it cannot
-        // vouch for.  (A negative M2 beyond rounding is the same condition.)
-        if (raw > 128.0 * m.m2 && raw > 0.0) {
-            hi = lo = istd = __uint_as_float(0x7fc00000u);
-            if (A.raise_word) atomicExch(A.raise_word, 1u);
-        }
+        float istd = (float)(1.0 / sqrt(m.m2 / A.M + A.eps));
         A.out0[c] = hi;
         A.out1[c] = lo;
         if (A.out2) A.out2[c] = lo;

@@ -30,17 +30,22 @@ def _as_f64_dev(t, dtype):
 
 # every workload on the path the library takes by itself; the two extremes of the single-launch kernels
 # (few huge planes, many tiny ones) also on the multi-sweep kernels a shape falls back to
-@pytest.mark.parametrize("name,fused", [("cfg1", 1), ("cfg2", 1), ("cfg3", 1), ("cfg4", 1), ("cfg4b", 1),
-                                        ("cfg1", 0), ("cfg3", 0)],
-                         ids=["cfg1", "cfg2", "cfg3", "cfg4", "cfg4b", "cfg1-sweeps", "cfg3-sweeps"])
-def test_full_size(name, fused):
+# (the channels-last workloads run on the multi-sweep kernels in any case: by default with the forward's statistics
+# from one sweep over x, and once more with a sweep each for the sums and the squared deviations)
+@pytest.mark.parametrize("name,fused,one_sweep", [("cfg1", 1, 1), ("cfg2", 1, 1), ("cfg3", 1, 1), ("cfg4", 1, 1), ("cfg4b", 1, 1),
+                                                  ("cfg1", 0, 1), ("cfg3", 0, 1), ("cfg4", 1, 0), ("cfg4b", 1, 0), ("cfg1", 0, 0)],
+                         ids=["cfg1", "cfg2", "cfg3", "cfg4", "cfg4b", "cfg1-sweeps", "cfg3-sweeps", "cfg4-two-pass", "cfg4b-two-pass",
+                              "cfg1-sweeps-two-pass"])
+def test_full_size(name, fused, one_sweep):
     from paper_1711_07240_amd import cgbn as L
-    old = L.cgbn_get_tuning("fused")
+    old = L.cgbn_get_tuning("fused"), L.cgbn_get_tuning("one_sweep_stats")
     L.cgbn_set_tuning("fused", fused)
+    L.cgbn_set_tuning("one_sweep_stats", one_sweep)
     try:
         _full_size(name, fused)
     finally:
-        L.cgbn_set_tuning("fused", old)
+        L.cgbn_set_tuning("fused", old[0])
+        L.cgbn_set_tuning("one_sweep_stats", old[1])
 
 
 def _full_size(name, fused):

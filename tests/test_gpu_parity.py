@@ -14,14 +14,19 @@ from gpu_harness import DEV, Problem, check_against_oracle, widen, to_dev, to_ho
 pytestmark = pytest.mark.gpu
 
 
-@pytest.fixture(autouse=True, params=[1, 0], ids=["fused", "sweeps"])
+@pytest.fixture(autouse=True, params=[(1, 1), (0, 1), (0, 0)], ids=["fused", "sweeps", "sweeps-two-pass"])
 def path(request):
-    """Every test runs twice: with the register-resident single-launch kernels
-    (where the shape allows them) and with the multi-sweep kernels only."""
-    old = L.cgbn_get_tuning("fused")
-    L.cgbn_set_tuning("fused", request.param)
-    yield request.param
-    L.cgbn_set_tuning("fused", old)
+    """Every test runs three times: with the register-resident single-launch kernels
+    (where the shape allows them), with the multi-sweep kernels only (their forward taking
+    its statistics from one sweep over x, the default), and with the multi-sweep kernels
+    and a sweep each for the sums and for the squared deviations.  Yields whether the
+    single-launch kernels are on."""
+    old = L.cgbn_get_tuning("fused"), L.cgbn_get_tuning("one_sweep_stats")
+    L.cgbn_set_tuning("fused", request.param[0])
+    L.cgbn_set_tuning("one_sweep_stats", request.param[1])
+    yield request.param[0]
+    L.cgbn_set_tuning("fused", old[0])
+    L.cgbn_set_tuning("one_sweep_stats", old[1])
 
 
 def oracle_all(x, dy, gamma, beta, eps, layout, dtype):

@@ -493,7 +493,20 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
     // values per row partial: a chunk of a plane (the last chunk shorter), a whole plane, or a pixel run of a shard
     if (p.layout == CGBN_NCHW) { A.row_mod = p.sp; A.row_full = p.wave_mode ? p.HW : p.L; A.row_total = p.HW; }
     else { A.row_mod = p.pps; A.row_full = p.PL; A.row_total = p.spix; }
-    dim3 grid((unsigned)((p.C + 3) / 4)), block(kThreads);
+    dim3 block(kThreads);
+    if (p.layout == CGBN_NHWC) {       // a row's channels side by side: 16 channels per workgroup
+        dim3 grid((unsigned)((p.C + 15) / 16));
+        switch (mode) {
+        case CM_MEAN:   hipLaunchKernelGGL((combine_rows_cl<CM_MEAN>), grid, block, 0, st, A); break;
+        case CM_INVSTD: hipLaunchKernelGGL((combine_rows_cl<CM_INVSTD>), grid, block, 0, st, A); break;
+        case CM_BWD:    hipLaunchKernelGGL((combine_rows_cl<CM_BWD>), grid, block, 0, st, A); break;
+        case CM_SHARDS2: hipLaunchKernelGGL((combine_rows_cl<CM_SHARDS2>), grid, block, 0, st, A); break;
+        case CM_MOMENTS: hipLaunchKernelGGL((combine_rows_cl<CM_MOMENTS>), grid, block, 0, st, A); break;
+        default:        hipLaunchKernelGGL((combine_rows_cl<CM_SHARDS1>), grid, block, 0, st, A); break;
+        }
+        return launched();
+    }
+    dim3 grid((unsigned)((p.C + 3) / 4));
     switch (mode) {
     case CM_MEAN:   hipLaunchKernelGGL((combine_rows<CM_MEAN>), grid, block, 0, st, A); break;
     case CM_INVSTD: hipLaunchKernelGGL((combine_rows<CM_INVSTD>), grid, block, 0, st, A); break;

@@ -895,14 +895,24 @@ __device__ __forceinline__ double shard_then_total(const float* pr, double* sh, 
 struct Moments {
     double n, mean, m2;
 };
+// 1/v in double precision without the division sequence: the hardware's float reciprocal, two Newton steps
+// (1e-7 -> 1e-14 -> rounding).  For counts, which are positive and far inside float range.
+__device__ __forceinline__ double rcp_count(double v)
+{
+    double y = (double)__builtin_amdgcn_rcpf((float)v);
+    y = y * (2.0 - v * y);
+    y = y * (2.0 - v * y);
+    return y;
+}
 __device__ __forceinline__ Moments merge_moments(const Moments& a, const Moments& b)
 {
     Moments r;
     r.n = a.n + b.n;
     if (r.n == 0.0) return a;
+    const double rn = rcp_count(r.n);
     const double d = b.mean - a.mean;
-    r.mean = a.mean + d * (b.n / r.n);
-    r.m2 = a.m2 + b.m2 + d * d * (a.n * b.n / r.n);
+    r.mean = a.mean + d * (b.n * rn);
+    r.m2 = a.m2 + b.m2 + d * d * (a.n * b.n * rn);
     return r;
 }
 
@@ -988,6 +998,117 @@ __global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
     } else if (MODE == CM_BWD) {
         A.out0[c] = (float)t0;
         A.out1[c] = (float)t1;
+    }
+}
+
+// The same for channels-last row partials ([rows][C]: a row's channels side by side).  There one wavefront per
+// channel would fetch every row from a different cache line; here a workgroup takes 16 neighbouring channels and
+// its 256 threads are 16 channels x 16 "row lanes".  Row lane j adds, for the shards j, j + 16, ... in turn, the
+// rows of the shard in order (the device sum of Algorithm 1, stored to the shard-sum arrays if wanted) and keeps
+// the running total of its shards; the 16 lane totals of a channel are then added in lane order (the reduce step).
+// Double precision, fixed order.  CM_MOMENTS: summaries merged pairwise instead of sums added, in the same order.
+template <int MODE>
+__global__ __launch_bounds__(kThreads) void combine_rows_cl(CombineArgs A)
+{
+    constexpr int Q = (MODE == CM_BWD || MODE == CM_SHARDS2 || MODE == CM_MOMENTS) ? 2 : 1;
+    __shared__ double tot[3][16][16];           // [what][row lane][channel]
+    const int t = threadIdx.x, cl = t & 15, rl = t >> 4;
+    const int c = blockIdx.x * 16 + cl;
+    if (A.clear_word && blockIdx.x == 0 && t == 0) *A.clear_word = 0u;
+    const bool live = c < A.C;
+    const double pivot = live ? pivot_of(A, c) : 0.0;
+    double t0 = 0.0, t1 = 0.0;
+    Moments mine = {0.0, 0.0, 0.0};
+    // CM_MOMENTS: a row holds row_full values, the last row of a run what is left
+    const double n_last = (double)(A.row_total - (A.row_mod - 1) * A.row_full);
+    const double r_full = MODE == CM_MOMENTS ? rcp_count((double)A.row_full) : 0.0;
+    const double r_last = MODE == CM_MOMENTS ? rcp_count(n_last) : 0.0;
+    if (live) {
+        const float* p0 = A.part0 + c;
+        const float* p1 = A.part1 + c;
+        for (int k = rl; k < A.K; k += 16) {
+            double a0 = 0.0, a1 = 0.0;
+            Moments sk = {0.0, 0.0, 0.0};
+            constexpr int B = 8;                 // rows fetched together
+            for (int r0 = 0; r0 < A.rps; r0 += B) {
+                float v0[B], v1[B];
+#pragma unroll
+                for (int u = 0; u < B; ++u) {
+                    const bool have = r0 + u < A.rps;
+                    const size_t o = have ? ((size_t)k * A.rps + r0 + u) * (size_t)A.C : 0;
+                    v0[u] = p0[o];
+                    v1[u] = Q == 2 ? p1[o] : 0.f;
+                }
+#pragma unroll
+                for (int u = 0; u < B; ++u) {
+                    if (r0 + u < A.rps) {
+                        if (MODE == CM_MOMENTS) {
+                            const long long row = (long long)k * A.rps + r0 + u;
+                            const bool last = row % A.row_mod == A.row_mod - 1;
+                            Moments m;
+                            m.n = last ? n_last : (double)A.row_full;
+                            m.mean = (double)v0[u] * (last ? r_last : r_full);        // about the pivot
+                            m.m2 = (double)v1[u];
+                            sk = merge_moments(sk, m);
+                        } else {
+                            a0 += (double)v0[u];
+                            a1 += (double)v1[u];
+                        }
+                    }
+                }
+            }
+            if (MODE == CM_MOMENTS) {
+                mine = merge_moments(mine, sk);
+            } else {
+                if (A.sh0) A.sh0[(size_t)k * A.C + c] = a0 + pivot * A.shard_count;
+                if (Q == 2 && A.sh1) A.sh1[(size_t)k * A.C + c] = a1;
+                t0 += a0;
+                t1 += a1;
+            }
+        }
+    }
+    if (MODE == CM_MOMENTS) {
+        tot[0][rl][cl] = mine.n;
+        tot[1][rl][cl] = mine.mean;
+        tot[2][rl][cl] = mine.m2;
+    } else {
+        tot[0][rl][cl] = t0;
+        tot[1][rl][cl] = t1;
+    }
+    __syncthreads();
+    if (rl != 0 || !live) return;
+    if (MODE == CM_MOMENTS) {
+        Moments m = {tot[0][0][cl], tot[1][0][cl], tot[2][0][cl]};
+        for (int j = 1; j < 16; ++j) {
+            Moments o = {tot[0][j][cl], tot[1][j][cl], tot[2][j][cl]};
+            m = merge_moments(m, o);
+        }
+        double mean = pivot + m.mean;
+        float hi = (float)mean;
+        float lo = (float)(mean - (double)hi);
+        A.out0[c] = hi;
+        A.out1[c] = lo;
+        if (A.out2) A.out2[c] = lo;
+        A.out3[c] = (float)(1.0 / sqrt(m.m2 / A.M + A.eps));
+        return;
+    }
+    double s0 = 0.0, s1 = 0.0;
+    for (int j = 0; j < 16; ++j) {
+        s0 += tot[0][j][cl];
+        s1 += tot[1][j][cl];
+    }
+    if (MODE == CM_MEAN) {
+        double m = pivot + s0 / A.M;
+        float hi = (float)m;
+        float lo = (float)(m - (double)hi);
+        A.out0[c] = hi;
+        A.out1[c] = lo;
+        if (A.out2) A.out2[c] = lo;
+    } else if (MODE == CM_INVSTD) {
+        A.out0[c] = (float)(1.0 / sqrt(s0 / A.M + A.eps));
+    } else if (MODE == CM_BWD) {
+        A.out0[c] = (float)s0;
+        A.out1[c] = (float)s1;
     }
 }
 

@@ -170,11 +170,11 @@ void make_fused_plan(const Tuning& T, int N, int C, long long HW, int K, int lay
         f->LPP = (int)((HW + (long long)kWave * E - 1) / ((long long)kWave * E));
         // register slots per plane: the smallest instantiated count that holds a plane and
         // leaves at most 16 planes per wavefront
-        static const int kSlotCounts[] = {2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 64, 128};
         int lppc = 0;
-        for (int cand : kSlotCounts)
+        for (int cand : kCgbnSlotCounts)
             if (cand >= f->LPP && cand * 16 >= R && cand <= R) { lppc = cand; break; }
         if (!lppc) return;
+        if (f->LPP <= cgbn_full_slots(lppc, R)) return;    // (cannot happen: the kernels rely on it, see the table)
         f->LPPC = lppc;
         // with few rows and shards to stage, further whole planes per wavefront go to LDS
         int lds_planes = 0;

@@ -50,6 +50,7 @@
 #pragma once
 
 #include "cgbn_kernels.h"
+#include "cgbn_fused_list.h"
 
 namespace cgbn {
 
@@ -543,6 +544,12 @@ __device__ __forceinline__ float load_scalar(const float* p, int i)
     return *reinterpret_cast<const_float*>(reinterpret_cast<uintptr_t>(p + uniform(i)));
 }
 
+// Makes the compiler forget what it knows about a register's contents, at no cost (the value stays where it
+// is).  The passes over a resident unit each unpack the same registers; where a pass is straight-line code
+// (slots that need no checks) the compiler would otherwise keep one pass's unpacked values alive for the
+// next and run out of registers (bfloat16 forward: up to 488 bytes of scratch per lane).
+__device__ __forceinline__ void forget(uint32_t& v) { asm volatile("" : "+v"(v)); }
+
 // Waits until every vector-memory access the wavefront has issued is done.  As the compiler's own
 // builtin (vmcnt 0; the other two counters at their maxima, i.e. not waited for), not as assembly
 // text: the compiler then knows that no load is outstanding afterwards.  Otherwise it may have to
@@ -606,6 +613,10 @@ struct Slots {
     static constexpr bool WGP = LPPC < 0;            // several whole planes per workgroup
     static constexpr int PPU = WGP ? -LPPC : 1;      // ... that many
     static constexpr int SPP = SMALL ? LPPC : 1;     // slots per plane
+    // leading slots of every plane that are full whatever shape this variant serves (see cgbn_full_slots):
+    // no length or lane checks there
+    static constexpr int FULL = SMALL ? cgbn_full_slots(LPPC, R) : 0;
+    static constexpr bool always_full(int s) { return SMALL && (s % SPP) < FULL; }
 
     static __device__ __forceinline__ void geometry(const FusedArgs& A, long long unit, UnitGeom& g)
     {
@@ -634,7 +645,7 @@ struct Slots {
     // is any lane of slot s in use (uniform)
     static __device__ __forceinline__ bool in_use(const FusedArgs& A, const UnitGeom& g, int s, int w)
     {
-        if (SMALL) return image(g, s, w) < g.n1 && (s % SPP) < A.LPP;
+        if (SMALL) return image(g, s, w) < g.n1 && (always_full(s) || (s % SPP) < A.LPP);
         if (WGP) return g.n0 + s / SPW < g.n1 && (s % SPW) * (kThreads * LB) < g.len;
         return s * (kThreads * LB) < g.len;
     }
@@ -651,7 +662,7 @@ struct Slots {
     }
     static __device__ __forceinline__ bool lane_ok(const UnitGeom& g, int s, unsigned loff)
     {
-        return (unsigned)slot_offset(s) + loff < (unsigned)g.len;
+        return always_full(s) || (unsigned)slot_offset(s) + loff < (unsigned)g.len;
     }
     static constexpr bool ends_plane(int s) { return SMALL && (s % SPP) == SPP - 1; }
     // workgroup-wide planes: slot s is the last of plane s / SPW (one row per plane, summed across the wavefronts)
@@ -743,6 +754,13 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
                 constexpr int s0 = decltype(s0_)::value, s1 = decltype(s1_)::value;
                 constexpr bool square = decltype(square_)::value;
                 float acc[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+                for (int s = s0; s < s1; ++s) {
+                    if (s < RS && SL::always_full(s)) {
+#pragma unroll
+                        for (int q = 0; q < W; ++q) forget(d[(s < RS ? s : 0) * W + q]);
+                    }
+                }
 #pragma unroll
                 for (int s = s0; s < s1; ++s) {
                     if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
@@ -899,6 +917,13 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
         } else {
             const unsigned loff = SL::lane_offset(t);
             const float gsc = uniform_f(load_scalar(A.gamma, c) * istd), bsh = load_scalar(A.beta, c);
+#pragma unroll
+            for (int s = 0; s < RS; ++s) {
+                if (SL::always_full(s)) {
+#pragma unroll
+                    for (int q = 0; q < W; ++q) forget(d[s * W + q]);
+                }
+            }
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {

@@ -31,3 +31,21 @@
 // to 4095 floats 1.3 to 1.6 times slower; the 24-slot variant, planes of 1075 to 1535 floats, 1.5 times faster).
 // Such shapes take the multi-sweep kernels for that call.
 #define CGBN_FUSED_RELU_BWD_F32_NARROW(X) X(4, 24)
+
+// The slot counts the host may choose for small planes, ascending: for a plane of LPP slots it takes the smallest
+// count >= LPP that leaves at most 16 planes per wavefront (count * 16 >= R, R the register slots per tensor) and
+// fits the registers (count <= R).  Hence a variant built for `lppc` slots only ever sees planes longer than the
+// next smaller admissible count: that many leading slots of every plane are full in every shape the variant
+// serves, and its kernels check neither the plane's length nor the lanes there.  A plane longer than the
+// registers (lppc > R: the last slots live in LDS) fills all R register slots.
+constexpr int kCgbnSlotCounts[] = {2, 3, 4, 5, 6, 8, 10, 12, 16, 24, 32, 64, 128};
+constexpr int cgbn_full_slots(int lppc, int R)
+{
+    if (lppc > R) return R;
+    int prev = 0;
+    for (int c : kCgbnSlotCounts) {
+        if (c >= lppc) break;
+        prev = c;
+    }
+    return prev * 16 >= R ? prev : 0;
+}

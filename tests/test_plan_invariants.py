@@ -38,6 +38,25 @@ def _built():
 BUILT = _built()
 
 
+def _slot_counts():
+    text = open(os.path.join(ROOT, "paper_1711_07240_amd", "csrc", "cgbn_fused_list.h")).read()
+    body = re.search(r"kCgbnSlotCounts\[\]\s*=\s*\{([^}]*)\}", text).group(1)
+    return [int(v) for v in body.split(",")]
+
+
+SLOT_COUNTS = _slot_counts()
+
+
+def _full_slots(lppc, R):
+    """Leading slots of every plane the kernels of a variant treat as full without looking (restated from the
+    rule: the host takes the smallest admissible slot count, so a plane is longer than the next smaller one)."""
+    if lppc > R:
+        return R
+    smaller = [c for c in SLOT_COUNTS if c < lppc]
+    prev = smaller[-1] if smaller else 0
+    return prev if prev * 16 >= R else 0
+
+
 def _ceil(a, b):
     return -(-a // b)
 
@@ -98,6 +117,9 @@ def _check_fused(shape, direction):
         assert big in (0, 2)
         LPP = g("LPP")
         assert LPP == _ceil(HW, WAVE * E) and LPP <= LPPC
+        full = _full_slots(LPPC, R)
+        assert full < LPP, "the kernels read the first `full` slots of a plane without any check"
+        assert full * WAVE * LB <= HW * eb, "... so those slots must lie wholly inside the plane"
         if LPPC > R:                                 # one plane per wavefront, its last slots in LDS
             assert big == 0 and LPPC == R + ldsw // Wd and LB >= 8
             per_wave = 1

@@ -402,7 +402,7 @@ def main():
                    "value_is": "minimum bytes of a step (each of x, y, dy, x, dx touched once = 5 tensors) / step time",
                    "min_bytes": 5 * Sb, "two_pass_sweep_bytes": 9 * Sb,
                    "tuning": {k: cgbn.cgbn_get_tuning(k) for k in
-                              ("chunk_bytes", "wave_plane_bytes", "piece_bytes", "map_piece_bytes", "reverse", "nt_store", "fused",
+                              ("chunk_bytes", "wave_plane_bytes", "tiny_planes", "piece_bytes", "map_piece_bytes", "reverse", "nt_store", "fused",
                                "big_lds", "stagger", "stagger_us", "stagger_phases", "one_sweep_stats", "cooperative", "wait_us")},
                    "single_launch": head["single_launch"]},
         "pct_of_peak_on_min_bytes": head["pct_of_peak_on_min_bytes"],

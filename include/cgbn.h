@@ -262,6 +262,8 @@ const char* cgbn_status_string(cgbn_status status);
  * CGBN_ERR_WORKSPACE before launching anything).
  *   "chunk_bytes"      NCHW: bytes of one plane handled by one workgroup
  *   "wave_plane_bytes" NCHW: planes up to this size are handled by one wavefront
+ *   "tiny_planes"      0/1 (default 1): NCHW planes of at most 2 KiB, C a multiple of 8: a workgroup of the
+ *                      multi-sweep kernels takes a run of 8 ... 256 planes of consecutive channels at once
  *   "piece_bytes"      NHWC reductions: bytes of one pixel range handled by one workgroup (0, the default:
  *                      chosen per shape so that the grid fills the device's compute units evenly)
  *   "map_piece_bytes"  NHWC normalise / dx: the same for the elementwise sweeps

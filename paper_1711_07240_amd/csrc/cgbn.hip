@@ -87,6 +87,7 @@ cgbn_status scratch_of_current_device(void** out)
 struct Tuning {
     long long chunk_bytes = 32768;       // NCHW: bytes of a plane per workgroup
     long long wave_plane_bytes = 16384;  // NCHW: planes up to this go one per wavefront
+    long long tiny_planes = 1;           // NCHW: planes of at most 2 KiB (C a multiple of 8) go several to a workgroup
     long long piece_bytes = 0;           // NHWC reductions: bytes of a pixel run per workgroup; 0 = chosen per shape (see reduce_pieces)
     long long map_piece_bytes = 131072;  // NHWC normalise / dx: the same for the elementwise sweeps
     long long reverse = 1;               // alternate sweep direction so a sweep starts on what the last one left in cache
@@ -137,6 +138,7 @@ struct Plan {
     double M;
     // NCHW
     int wave_mode, L, sp;
+    int tiny, tg;         // tiny planes: `tg` planes of consecutive channels per workgroup
     // NHWC
     int cv, TW, ctiles, rpp, PL, pps;
     int PLm, ppsm;        // pixel runs of the elementwise sweeps (no rows to keep few)
@@ -313,7 +315,16 @@ cgbn_status make_plan(const Tuning& T, int N, int C, int H, int W, int layout, i
     const int full_vec = 16 / p->eb;
     if (layout == CGBN_NCHW) {
         p->vec = full_vec;
-        if (HW * p->eb <= T.wave_plane_bytes) {
+        if (T.tiny_planes && HW * p->eb <= kTinyPlaneBytes && C % 8 == 0) {
+            // several planes of consecutive channels per workgroup: the most that fit the LDS stage, as a power of two
+            int tg = 256;
+            while (tg > 8 && (long long)tg * HW * p->eb > kTinyStageBytes) tg >>= 1;
+            p->tiny = 1;
+            p->tg = tg;
+            p->L = (int)HW;
+            p->sp = 1;
+            p->grid = (long long)N * ((C + tg - 1) / tg);
+        } else if (HW * p->eb <= T.wave_plane_bytes) {
             p->wave_mode = 1;
             p->L = (int)HW;
             p->sp = 1;
@@ -369,6 +380,14 @@ cgbn_status make_plan(const Tuning& T, int N, int C, int H, int W, int layout, i
     p->G = G;
     make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, kFusedLdsWordsBigSmall, &p->ff);
     make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, kFusedLdsWordsBigSmall / 2, &p->fb);
+    // Tiny planes that would fill at most half of the register slots a single-launch variant reserves for a plane
+    // run faster through the multi-sweep kernels for tiny planes (measured, 256 images: fp32 7x7 x 1024 channels
+    // 46 / 58 us against 132 / 105; bf16 14x14 x 1024 channels 85 / 113 against 126 / 125; fp32 14x14 x 256
+    // channels, half full: level; fuller than that the single launch wins)
+    if (p->tiny) {
+        for (FusedPlan* f : {&p->ff, &p->fb})
+            if (f->ok && f->LPPC > 0 && 2 * f->LPP <= f->LPPC) f->ok = 0;
+    }
     int max_rows = p->rows;
     if (p->ff.ok && p->ff.rows > max_rows) max_rows = p->ff.rows;
     if (p->fb.ok && p->fb.rows > max_rows) max_rows = p->fb.rows;
@@ -407,6 +426,7 @@ SweepArgs sweep_args(const Plan& p)
     A.L = p.L; A.sp = p.sp;
     A.cv = p.cv; A.TW = p.TW; A.ctiles = p.ctiles; A.rpp = p.rpp; A.PL = p.PL; A.pps = p.pps;
     A.spix = p.spix;
+    A.tg = p.tg;
     A.pivot_stride = p.layout == CGBN_NCHW ? p.HW : 1;
     A.inv_M = (float)(1.0 / p.M);
     A.nt = (int)p.t.nt_store;
@@ -417,7 +437,8 @@ template <typename T, int OP> void launch_reduce_t(const Plan& p, const SweepArg
 {
     dim3 grid((unsigned)p.grid), block(kThreads);
     if (p.layout == CGBN_NCHW) {
-        if (p.wave_mode) hipLaunchKernelGGL((nchw_reduce_wave<T, OP>), grid, block, 0, st, A);
+        if (p.tiny) hipLaunchKernelGGL((nchw_reduce_tiny<T, OP>), grid, block, 0, st, A);
+        else if (p.wave_mode) hipLaunchKernelGGL((nchw_reduce_wave<T, OP>), grid, block, 0, st, A);
         else hipLaunchKernelGGL((nchw_reduce_block<T, OP>), grid, block, 0, st, A);
     } else {
         if (p.vec == 1) hipLaunchKernelGGL((nhwc_reduce<T, 1, OP>), grid, block, 0, st, A);
@@ -430,7 +451,8 @@ template <typename T, int EL> void launch_map_t(const Plan& p, const SweepArgs& 
     dim3 block(kThreads);
     if (p.layout == CGBN_NCHW) {
         dim3 grid((unsigned)p.grid);
-        if (p.wave_mode) hipLaunchKernelGGL((nchw_map_wave<T, EL>), grid, block, 0, st, A);
+        if (p.tiny) hipLaunchKernelGGL((nchw_map_tiny<T, EL>), grid, block, 0, st, A);
+        else if (p.wave_mode) hipLaunchKernelGGL((nchw_map_wave<T, EL>), grid, block, 0, st, A);
         else hipLaunchKernelGGL((nchw_map_block<T, EL>), grid, block, 0, st, A);
     } else {
         dim3 grid((unsigned)p.gridm);
@@ -491,7 +513,7 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
     if (p.layout == CGBN_NCHW) { A.cs = p.rows; A.rs = 1; } else { A.cs = 1; A.rs = p.C; }
     A.clear_word = reinterpret_cast<unsigned*>(ws + p.off_sync) + 1;
     // values per row partial: a chunk of a plane (the last chunk shorter), a whole plane, or a pixel run of a shard
-    if (p.layout == CGBN_NCHW) { A.row_mod = p.sp; A.row_full = p.wave_mode ? p.HW : p.L; A.row_total = p.HW; }
+    if (p.layout == CGBN_NCHW) { A.row_mod = p.sp; A.row_full = (p.wave_mode || p.tiny) ? p.HW : p.L; A.row_total = p.HW; }
     else { A.row_mod = p.pps; A.row_full = p.PL; A.row_total = p.spix; }
     dim3 block(kThreads);
     if (p.layout == CGBN_NHWC) {       // a row's channels side by side: 16 channels per workgroup
@@ -1080,6 +1102,7 @@ static long long* tuning_slot(const char* key)
     if (!key) return nullptr;
     if (!std::strcmp(key, "chunk_bytes")) return &g_tune.chunk_bytes;
     if (!std::strcmp(key, "wave_plane_bytes")) return &g_tune.wave_plane_bytes;
+    if (!std::strcmp(key, "tiny_planes")) return &g_tune.tiny_planes;
     if (!std::strcmp(key, "piece_bytes")) return &g_tune.piece_bytes;
     if (!std::strcmp(key, "map_piece_bytes")) return &g_tune.map_piece_bytes;
     if (!std::strcmp(key, "reverse")) return &g_tune.reverse;
@@ -1102,7 +1125,7 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
     long long* slot = tuning_slot(key);
     if (!slot) return CGBN_ERR_TUNING;
     if (slot == &g_tune.reverse || slot == &g_tune.nt_store || slot == &g_tune.fused || slot == &g_tune.one_sweep_stats ||
-        slot == &g_tune.cooperative || slot == &g_tune.big_lds || slot == &g_tune.stagger) {
+        slot == &g_tune.cooperative || slot == &g_tune.big_lds || slot == &g_tune.stagger || slot == &g_tune.tiny_planes) {
         if (value != 0 && value != 1) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.spin_limit) {
         if (value < 0 || value > 0xffffffffLL) return CGBN_ERR_TUNING;
@@ -1166,6 +1189,8 @@ long long cgbn_plan_get(int N, int C, int H, int W, cgbn_layout layout, cgbn_dty
         return -1;
     }
     if (!std::strcmp(key, "wave_mode")) return p.wave_mode;
+    if (!std::strcmp(key, "tiny")) return p.tiny;
+    if (!std::strcmp(key, "tg")) return p.tg;
     if (!std::strcmp(key, "L")) return p.L;
     if (!std::strcmp(key, "sp")) return p.sp;
     if (!std::strcmp(key, "vec")) return p.vec;

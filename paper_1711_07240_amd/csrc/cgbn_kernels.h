@@ -66,6 +66,7 @@ struct SweepArgs {
     int N, C, HW, rows;
     // NCHW
     int L, sp;                // chunk elements, chunks per plane
+    int tg;                   // tiny planes: planes per workgroup (a power of two, 8 ... 256)
     // NHWC
     int cv, TW, ctiles, rpp, PL, pps;
     long long spix;           // pixels per shard
@@ -104,6 +105,8 @@ template <> struct Elem<float> {
         f32x4 v = *reinterpret_cast<const f32x4*>(p);
         f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
     }
+    typedef f32x4 Raw;       // 16 bytes as they are stored
+    static __device__ __forceinline__ Raw load_raw(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
     static __device__ __forceinline__ void storev(float* p, const float (&f)[4], int nt)
     {
         f32x4 v = {f[0], f[1], f[2], f[3]};
@@ -124,6 +127,8 @@ template <> struct Elem<bf16_t> {
         f[4] = __uint_as_float(v.z << 16); f[5] = __uint_as_float(v.z & 0xffff0000u);
         f[6] = __uint_as_float(v.w << 16); f[7] = __uint_as_float(v.w & 0xffff0000u);
     }
+    typedef u32x4 Raw;
+    static __device__ __forceinline__ Raw load_raw(const bf16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
     static __device__ __forceinline__ void storev(bf16_t* p, const float (&f)[8], int nt)
     {
         u32x4 v;
@@ -608,6 +613,143 @@ __global__ __launch_bounds__(kThreads) void nchw_map_wave(SweepArgs A)
     f.k = map_consts<EL>(A, c);
     f.nt = A.nt;
     walk_segment<kWave, VEC>(plane * A.HW, A.HW, lane, A.S, f);
+}
+
+// --------------------------------------------------------------------------
+// NCHW, tiny planes (at most kTinyPlaneBytes each, C a multiple of 8)
+// --------------------------------------------------------------------------
+// A wavefront per plane wastes most of its lanes on a plane of a few dozen values, and a launch of
+// N * C / 4 workgroups that each fetch a hundred bytes is bound by dispatch, not by memory.  Here a
+// workgroup takes `tg` planes of consecutive channels of one image: one contiguous, 16-byte aligned run of
+// memory (8 planes of any size are a multiple of 16 bytes, and so is an image when C is a multiple of 8).
+// Reductions stage the run in LDS with 16-byte loads, then 256 / tg neighbouring threads share a plane;
+// the elementwise sweeps walk the run in vectors and look the channel of every element up.
+
+constexpr int kTinyPlaneBytes = 2048;
+constexpr int kTinyStageBytes = 16384;       // LDS per staged tensor: tg * plane bytes never exceeds it
+
+// `tp` neighbouring lanes (a power of two <= 64, aligned) add their values in a fixed tree; all get the sum
+__device__ __forceinline__ float group_sum(float v, int tp)
+{
+    for (int off = 1; off < tp; off <<= 1) v += __shfl_xor(v, off);
+    return v;
+}
+__device__ __forceinline__ Run group_run_join(Run mine, int tp, int lane)
+{
+    for (int off = 1; off < tp; off <<= 1) {
+        Run other;
+        other.n = __shfl_xor(mine.n, off);
+        other.S = __shfl_xor(mine.S, off);
+        other.M2 = __shfl_xor(mine.M2, off);
+        mine = (lane & off) ? run_join(other, mine) : run_join(mine, other);
+    }
+    return mine;
+}
+
+template <typename T, int OP>
+__global__ __launch_bounds__(kThreads) void nchw_reduce_tiny(SweepArgs A)
+{
+    constexpr int VEC = Elem<T>::VEC;
+    constexpr int Q = op_sums(OP);
+    constexpr bool DY = op_has_dy(OP), Y = op_has_y(OP);
+    using Raw = typename Elem<T>::Raw;
+    __shared__ Raw sx[kTinyStageBytes / 16];
+    __shared__ Raw sd[DY ? kTinyStageBytes / 16 : 1];
+    __shared__ Raw sy[Y ? kTinyStageBytes / 16 : 1];
+    const long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
+    const int groups = (A.C + A.tg - 1) / A.tg;
+    const int n = (int)(b / groups), c0 = (int)(b % groups) * A.tg;
+    const int gc = min(A.tg, A.C - c0);                       // planes of this workgroup (a multiple of 8)
+    const long long e0 = ((long long)n * A.C + c0) * A.HW;    // its first element
+    const int nvec = gc * A.HW / VEC;
+    const int t = threadIdx.x;
+    if (n >= A.N || e0 < 0 || e0 + (long long)gc * A.HW > A.S) return;     // never outside the tensor
+    for (int v = t; v < nvec; v += kThreads) {
+        sx[v] = Elem<T>::load_raw(static_cast<const T*>(A.x) + e0 + (long long)v * VEC);
+        if (DY) sd[v] = Elem<T>::load_raw(static_cast<const T*>(A.dy) + e0 + (long long)v * VEC);
+        if (Y) sy[v] = Elem<T>::load_raw(static_cast<const T*>(A.aux) + e0 + (long long)v * VEC);
+    }
+    __syncthreads();
+    const int tp = kThreads / A.tg;                           // threads per plane (1 ... 32)
+    const int pl = t / tp, sub = t % tp;
+    const bool live = pl < gc;
+    const int c = c0 + (live ? pl : 0);
+    const ChanConst k = reduce_consts<T, OP>(A, c);
+    const T* px = reinterpret_cast<const T*>(sx) + pl * A.HW;
+    const T* pd = reinterpret_cast<const T*>(sd) + pl * A.HW;
+    const T* py = reinterpret_cast<const T*>(sy) + pl * A.HW;
+    float a0 = 0.f, a1 = 0.f;
+    Run run = {0.f, 0.f, 0.f};
+    if (live) {
+        for (int j = sub; j < A.HW; j += tp) {
+            const float xv = Elem<T>::load1(px + j);
+            if constexpr (OP == OP_MOMENTS) {
+                float v[1] = {xv - k.mu};
+                run_feed<1>(run, v);
+            } else {
+                accumulate<OP>(k, xv, DY ? Elem<T>::load1(pd + j) : 0.f, Y ? Elem<T>::load1(py + j) : 0.f, a0, a1);
+            }
+        }
+    }
+    // (a plane's threads are neighbouring lanes of one wavefront: tp divides 64)
+    const size_t o = (size_t)c * A.rows + n;
+    if constexpr (OP == OP_MOMENTS) {
+        run = group_run_join(run, tp, t & (kWave - 1));
+        if (live && sub == 0) { A.part0[o] = run.S; A.part1[o] = run.M2; }
+    } else {
+        a0 = group_sum(a0, tp);
+        if (Q == 2) a1 = group_sum(a1, tp);
+        if (live && sub == 0) {
+            A.part0[o] = a0;
+            if (Q == 2) A.part1[o] = a1;
+        }
+    }
+}
+
+template <typename T, int EL>
+__global__ __launch_bounds__(kThreads) void nchw_map_tiny(SweepArgs A)
+{
+    constexpr int VEC = Elem<T>::VEC;
+    constexpr bool IN2 = el_has_2(EL), IN3 = el_has_3(EL);
+    __shared__ ChanConst sk[256];
+    const long long b = A.reverse ? (long long)gridDim.x - 1 - blockIdx.x : (long long)blockIdx.x;
+    const int groups = (A.C + A.tg - 1) / A.tg;
+    const int n = (int)(b / groups), c0 = (int)(b % groups) * A.tg;
+    const int gc = min(A.tg, A.C - c0);
+    const long long e0 = ((long long)n * A.C + c0) * A.HW;
+    const int nvec = gc * A.HW / VEC;
+    const int t = threadIdx.x;
+    if (n >= A.N || e0 < 0 || e0 + (long long)gc * A.HW > A.S) return;
+    if (t < gc) sk[t] = map_consts<EL>(A, c0 + t);
+    __syncthreads();
+    const T* x = static_cast<const T*>(A.x) + e0;
+    const T* v2p = static_cast<const T*>(A.dy) + e0;
+    const T* v3p = static_cast<const T*>(A.aux) + e0;
+    T* out = static_cast<T*>(A.out) + e0;
+    T* out2 = A.out2 ? static_cast<T*>(A.out2) + e0 : nullptr;
+    const float inv_hw = 1.0f / (float)A.HW;
+    for (int v = t; v < nvec; v += kThreads) {
+        float xv[VEC], v2[VEC], v3[VEC], r[VEC], dz[VEC];
+        Elem<T>::loadv(x + (long long)v * VEC, xv);
+        if (IN2) Elem<T>::loadv(v2p + (long long)v * VEC, v2);
+        if (IN3) Elem<T>::loadv(v3p + (long long)v * VEC, v3);
+        // plane of the vector's first element: the float quotient is exact to within one for indices below
+        // 2^23, the two corrections settle it
+        const int i0 = v * VEC;
+        int pl = (int)((float)i0 * inv_hw);
+        int rem = i0 - pl * A.HW;
+        if (rem < 0) { rem += A.HW; --pl; }
+        if (rem >= A.HW) { rem -= A.HW; ++pl; }
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            while (rem >= A.HW) { rem -= A.HW; ++pl; }        // (planes may be shorter than a vector)
+            dz[e] = 0.f;
+            r[e] = map_value<EL>(sk[pl], xv[e], IN2 ? v2[e] : 0.f, IN3 ? v3[e] : 0.f, dz[e]);
+            ++rem;
+        }
+        Elem<T>::storev(out + (long long)v * VEC, r, A.nt);
+        if (IN3 && out2) Elem<T>::storev(out2 + (long long)v * VEC, dz, A.nt);
+    }
 }
 
 // --------------------------------------------------------------------------

@@ -26,6 +26,8 @@ CASES = [
     ("nhwc-bf16", 4, 128, 13, 10, "NHWC", "bf16"),
     ("nhwc-bf16-scalar", 2, 10, 5, 3, "NHWC", "bf16"),
     ("one-pixel", 5, 8, 1, 1, "NCHW", "f32"),
+    ("nchw-bf16-tiny-7x7", 4, 64, 7, 7, "NCHW", "bf16"),      # runs of tiny planes per workgroup (C a multiple of 8)
+    ("nchw-f32-tiny-ragged-group", 2, 264, 3, 3, "NCHW", "f32"),
 ]
 
 

@@ -123,6 +123,18 @@ SMALL = [
     ("nhwc-f32-c256-long-shard", dict(N=2, C=256, H=60, W=70, K=1, layout="NHWC", dtype="f32")),
     ("nhwc-bf16-c128", dict(N=4, C=128, H=33, W=35, K=2, layout="NHWC", dtype="bf16")),
     ("nhwc-bf16-c64-long-shard", dict(N=2, C=64, H=50, W=41, K=2, layout="NHWC", dtype="bf16")),
+    # tiny NCHW planes, C a multiple of 8: a run of planes of consecutive channels per workgroup (multi-sweep path);
+    # odd element counts in bf16, planes shorter than a 16-byte vector, a ragged last channel group, one pixel
+    ("nchw-bf16-tiny-7x7", dict(N=8, C=64, H=7, W=7, K=4, layout="NCHW", dtype="bf16")),
+    ("nchw-f32-tiny-7x7", dict(N=6, C=40, H=7, W=7, K=3, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-tiny-13x21-odd", dict(N=4, C=24, H=13, W=21, K=2, layout="NCHW", dtype="bf16")),
+    ("nchw-bf16-tiny-2x2", dict(N=8, C=16, H=2, W=2, K=2, layout="NCHW", dtype="bf16")),
+    ("nchw-f32-tiny-1x3", dict(N=4, C=8, H=1, W=3, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-f32-tiny-1x1", dict(N=16, C=32, H=1, W=1, K=4, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-tiny-1x1", dict(N=16, C=8, H=1, W=1, K=8, layout="NCHW", dtype="bf16")),
+    ("nchw-bf16-tiny-ragged-group", dict(N=3, C=264, H=5, W=5, K=3, layout="NCHW", dtype="bf16")),
+    ("nchw-f32-tiny-2KiB", dict(N=4, C=16, H=16, W=32, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-tiny-14x14-c1024", dict(N=2, C=1024, H=14, W=14, K=2, layout="NCHW", dtype="bf16")),
     # degenerate shapes
     ("one-image-per-shard", dict(N=6, C=4, H=8, W=8, K=6, layout="NCHW", dtype="f32")),
     ("single-image", dict(N=1, C=3, H=20, W=20, K=1, layout="NCHW", dtype="f32")),

@@ -73,7 +73,14 @@ def _check_sweeps(shape):
     rows, rps = g("rows"), g("rps")
     assert rows == rps * K
     if layout == "NCHW":
-        if g("wave_mode"):
+        if g("tiny"):
+            tg = g("tg")
+            assert HW * eb <= 2048 and C % 8 == 0, "tiny planes: a workgroup's run must start and end on 16 bytes"
+            assert tg in (8, 16, 32, 64, 128, 256) and tg * HW * eb <= 16384, "the run must fit its LDS stage"
+            assert tg == 256 or 2 * tg * HW * eb > 16384, "... and be the longest that does"
+            assert g("L") == HW and g("sp") == 1 and not g("wave_mode")
+            assert g("grid") == N * _ceil(C, tg) and rows == N
+        elif g("wave_mode"):
             assert HW * eb <= 16384 and g("L") == HW and g("sp") == 1
             assert g("grid") == _ceil(N * C, 4) and rows == N
         else:

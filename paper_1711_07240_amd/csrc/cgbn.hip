@@ -380,13 +380,13 @@ cgbn_status make_plan(const Tuning& T, int N, int C, int H, int W, int layout, i
     p->G = G;
     make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, kFusedLdsWordsBigSmall, &p->ff);
     make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, kFusedLdsWordsBigSmall / 2, &p->fb);
-    // Tiny planes that would fill at most half of the register slots a single-launch variant reserves for a plane
-    // run faster through the multi-sweep kernels for tiny planes (measured, 256 images: fp32 7x7 x 1024 channels
-    // 46 / 58 us against 132 / 105; bf16 14x14 x 1024 channels 85 / 113 against 126 / 125; fp32 14x14 x 256
-    // channels, half full: level; fuller than that the single launch wins)
+    // Tiny planes that would fill less than half of the register slots a single-launch variant reserves for a plane
+    // run faster through the multi-sweep kernels for tiny planes (measured, 256 images, fwd / bwd us: fp32 7x7 x 1024
+    // channels 46 / 58 against 132 / 105; bf16 14x14 x 1024 channels, forward, 85 against 126.  Half full, fp32
+    // 14x14: level at 256 channels, the single launch ahead at 1024, 131 / 195 against 153 / 222)
     if (p->tiny) {
         for (FusedPlan* f : {&p->ff, &p->fb})
-            if (f->ok && f->LPPC > 0 && 2 * f->LPP <= f->LPPC) f->ok = 0;
+            if (f->ok && f->LPPC > 0 && 2 * f->LPP < f->LPPC) f->ok = 0;
     }
     int max_rows = p->rows;
     if (p->ff.ok && p->ff.rows > max_rows) max_rows = p->ff.rows;

@@ -266,7 +266,8 @@ const char* cgbn_status_string(cgbn_status status);
  *                      multi-sweep kernels takes a run of 8 ... 256 planes of consecutive channels at once
  *   "piece_bytes"      NHWC reductions: bytes of one pixel range handled by one workgroup (0, the default:
  *                      chosen per shape so that the grid fills the device's compute units evenly)
- *   "map_piece_bytes"  NHWC normalise / dx: the same for the elementwise sweeps
+ *   "map_piece_bytes"  NHWC normalise / dx: the same for the elementwise sweeps (0, the default: 128 KiB for
+ *                      bfloat16; for float 64 KiB where the sweep reads one tensor, 32 KiB where it reads more)
  *   "reverse"          0/1: alternate the sweep direction between consecutive sweeps
  *   "nt_store"         0/1: non-temporal stores for y and dx
  *   "fused"            0/1: register-resident single-launch forward/backward (NCHW)

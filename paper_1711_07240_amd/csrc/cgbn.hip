@@ -89,7 +89,7 @@ struct Tuning {
     long long wave_plane_bytes = 16384;  // NCHW: planes up to this go one per wavefront
     long long tiny_planes = 1;           // NCHW: planes of at most 2 KiB (C a multiple of 8) go several to a workgroup
     long long piece_bytes = 0;           // NHWC reductions: bytes of a pixel run per workgroup; 0 = chosen per shape (see reduce_pieces)
-    long long map_piece_bytes = 131072;  // NHWC normalise / dx: the same for the elementwise sweeps
+    long long map_piece_bytes = 0;       // NHWC normalise / dx: the same for the elementwise sweeps; 0 = chosen per dtype and sweep (see map_pieces)
     long long reverse = 1;               // alternate sweep direction so a sweep starts on what the last one left in cache
     long long nt_store = 1;              // non-temporal stores for y and dx
     long long fused = 1;                 // register-resident single-launch path where the shape allows it
@@ -141,8 +141,9 @@ struct Plan {
     int tiny, tg;         // tiny planes: `tg` planes of consecutive channels per workgroup
     // NHWC
     int cv, TW, ctiles, rpp, PL, pps;
-    int PLm, ppsm;        // pixel runs of the elementwise sweeps (no rows to keep few)
-    long long spix, gridm;
+    int PLm, ppsm;        // pixel runs of the elementwise sweeps (no rows to keep few): one input tensor ...
+    int PLm2, ppsm2;      // ... and two or three (dx; the shortcut and ReLU variants)
+    long long spix, gridm, gridm2;
     // partial sums
     int rows, rps, G;
     long long grid;       // workgroups of one sweep
@@ -363,16 +364,22 @@ cgbn_status make_plan(const Tuning& T, int N, int C, int H, int W, int layout, i
         p->rows = (int)(pps * K);
         p->rps = (int)pps;
         p->grid = (long long)p->rows * p->ctiles;
-        long long PLm = T.map_piece_bytes / ((long long)C * p->eb);
-        PLm -= PLm % (4 * p->rpp);
-        if (PLm < 4 * p->rpp) PLm = 4 * p->rpp;
-        if (PLm > p->spix) PLm = p->spix;
-        p->PLm = (int)PLm;
-        long long ppsm = (p->spix + PLm - 1) / PLm;
-        if (ppsm * K > 0x3fffffffLL) return CGBN_ERR_SHAPE;
-        p->ppsm = (int)ppsm;
-        p->gridm = ppsm * K * p->ctiles;
-        if (p->gridm > 0x7fffffffLL) return CGBN_ERR_SHAPE;
+        // Pixel runs of the elementwise sweeps.  Measured (fwd normalise / bwd dx, us): bf16 64x50x84x512 64 KiB 186 / 288,
+        // 128 KiB 168 / 285, 256 KiB 173 / 296; fp32 16x50x84x1024 32 KiB 175 / 260, 64 KiB 157 / 270, 128 KiB 159 / 274
+        // (the same order on 64, 256 and 2048 channels): bf16 128 KiB; fp32 64 KiB with one input tensor, 32 KiB with more.
+        for (int two = 0; two < 2; ++two) {
+            const long long bytes = T.map_piece_bytes > 0 ? T.map_piece_bytes : p->eb == 2 ? 131072 : two ? 32768 : 65536;
+            long long PLm = bytes / ((long long)C * p->eb);
+            PLm -= PLm % (4 * p->rpp);
+            if (PLm < 4 * p->rpp) PLm = 4 * p->rpp;
+            if (PLm > p->spix) PLm = p->spix;
+            long long ppsm = (p->spix + PLm - 1) / PLm;
+            if (ppsm * K > 0x3fffffffLL) return CGBN_ERR_SHAPE;
+            const long long gridm = ppsm * K * p->ctiles;
+            if (gridm > 0x7fffffffLL) return CGBN_ERR_SHAPE;
+            if (two) { p->PLm2 = (int)PLm; p->ppsm2 = (int)ppsm; p->gridm2 = gridm; }
+            else { p->PLm = (int)PLm; p->ppsm = (int)ppsm; p->gridm = gridm; }
+        }
     }
     if (p->grid > 0x7fffffffLL || (long long)p->rows * C > (1LL << 33)) return CGBN_ERR_SHAPE;
     int G = 1;
@@ -455,10 +462,11 @@ template <typename T, int EL> void launch_map_t(const Plan& p, const SweepArgs& 
         else if (p.wave_mode) hipLaunchKernelGGL((nchw_map_wave<T, EL>), grid, block, 0, st, A);
         else hipLaunchKernelGGL((nchw_map_block<T, EL>), grid, block, 0, st, A);
     } else {
-        dim3 grid((unsigned)p.gridm);
+        constexpr bool more_inputs = el_has_2(EL) || el_has_3(EL);
+        dim3 grid((unsigned)(more_inputs ? p.gridm2 : p.gridm));
         SweepArgs B = A;              // the elementwise sweeps cut the pixel runs their own way
-        B.PL = p.PLm;
-        B.pps = p.ppsm;
+        B.PL = more_inputs ? p.PLm2 : p.PLm;
+        B.pps = more_inputs ? p.ppsm2 : p.ppsm;
         if (p.vec == 1) hipLaunchKernelGGL((nhwc_map<T, 1, EL>), grid, block, 0, st, B);
         else hipLaunchKernelGGL((nhwc_map<T, Elem<T>::VEC, EL>), grid, block, 0, st, B);
     }
@@ -1139,7 +1147,7 @@ cgbn_status cgbn_set_tuning(const char* key, long long value)
         if (value < 0 || value > (1LL << 20)) return CGBN_ERR_TUNING;
     } else if (slot == &g_tune.wave_plane_bytes) {
         if (value < 0 || value > (1LL << 20)) return CGBN_ERR_TUNING;
-    } else if (slot == &g_tune.piece_bytes && value == 0) {
+    } else if ((slot == &g_tune.piece_bytes || slot == &g_tune.map_piece_bytes) && value == 0) {
         // chosen per shape
     } else if (value < 4096 || value > (1LL << 26)) {
         return CGBN_ERR_TUNING;
@@ -1202,6 +1210,9 @@ long long cgbn_plan_get(int N, int C, int H, int W, cgbn_layout layout, cgbn_dty
     if (!std::strcmp(key, "pps")) return p.pps;
     if (!std::strcmp(key, "PLm")) return p.PLm;
     if (!std::strcmp(key, "ppsm")) return p.ppsm;
+    if (!std::strcmp(key, "PLm2")) return p.PLm2;
+    if (!std::strcmp(key, "ppsm2")) return p.ppsm2;
+    if (!std::strcmp(key, "gridm2")) return p.gridm2;
     if (!std::strcmp(key, "rows")) return p.rows;
     if (!std::strcmp(key, "rps")) return p.rps;
     if (!std::strcmp(key, "G")) return p.G;

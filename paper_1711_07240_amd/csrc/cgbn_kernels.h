@@ -924,20 +924,23 @@ __global__ __launch_bounds__(kThreads) void nhwc_map(SweepArgs A)
     const long long C = A.C;
     const int rpp = A.rpp;
     int i = r;
-    for (; i + 3 * rpp < npix; i += 4 * rpp) {
-        float xv[4][V], v2[4][V], v3[4][V];
+    // loads in flight per lane and tensor: as many as the registers allow next to the other operands (measured on
+    // 64 x 50 x 84 x 512 bf16, normalise / dx: 4 each 110 / 166 us, 16 / 8 99 / 160)
+    constexpr int UNR = IN3 ? 4 : IN2 ? 8 : 16;
+    for (; i + (UNR - 1) * rpp < npix; i += UNR * rpp) {
+        float xv[UNR][V], v2[UNR][V], v3[UNR][V];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) Access<T, V>::load(px + (long long)(i + u * rpp) * C, xv[u]);
+        for (int u = 0; u < UNR; ++u) Access<T, V>::load(px + (long long)(i + u * rpp) * C, xv[u]);
         if (IN2) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, v2[u]);
+            for (int u = 0; u < UNR; ++u) Access<T, V>::load(pd + (long long)(i + u * rpp) * C, v2[u]);
         }
         if (IN3) {
 #pragma unroll
-            for (int u = 0; u < 4; ++u) Access<T, V>::load(py + (long long)(i + u * rpp) * C, v3[u]);
+            for (int u = 0; u < UNR; ++u) Access<T, V>::load(py + (long long)(i + u * rpp) * C, v3[u]);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < UNR; ++u) {
             float o[V], dz[V];
 #pragma unroll
             for (int e = 0; e < V; ++e) {

@@ -95,11 +95,11 @@ def _check_sweeps(shape):
         TW, ctiles, rpp = g("TW"), g("ctiles"), g("rpp")
         assert TW == min(C // vec, THREADS) and ctiles == _ceil(C // vec, TW) and rpp == THREADS // TW >= 1
         spix = ips * HW
-        for pl, pp in (("PL", "pps"), ("PLm", "ppsm")):
+        for pl, pp in (("PL", "pps"), ("PLm", "ppsm"), ("PLm2", "ppsm2")):
             PL, pps = g(pl), g(pp)
             assert 1 <= PL <= spix and pps == _ceil(spix, PL) and (pps - 1) * PL < spix
             assert PL == spix or PL % (4 * rpp) == 0
-        assert rows == g("pps") * K and g("grid") == rows * ctiles and g("gridm") == g("ppsm") * K * ctiles
+        assert rows == g("pps") * K and g("grid") == rows * ctiles and g("gridm") == g("ppsm") * K * ctiles and g("gridm2") == g("ppsm2") * K * ctiles
     G = g("G")
     assert G in (1, 2, 4, 8, 16, 32, 64) and G >= min(rps, WAVE) and (G == 1 or G // 2 < rps)
     return rows

@@ -39,6 +39,12 @@ CGBN_DECL_FX(16, 0, 1)
 CGBN_DECL_BX(16, 0, 1)
 CGBN_DECL_FX(16, -2, 1)
 CGBN_DECL_BX(16, -2, 1)
+#define CGBN_DECL_F1(LB_, LPPC_) CGBN_DECL_FX(LB_, LPPC_, 1)
+#define CGBN_DECL_B1(LB_, LPPC_) CGBN_DECL_BX(LB_, LPPC_, 1)
+CGBN_FUSED_WGP_FORWARD(CGBN_DECL_F1)
+CGBN_FUSED_WGP_BACKWARD(CGBN_DECL_B1)
+#undef CGBN_DECL_F1
+#undef CGBN_DECL_B1
 #define CGBN_DECL_F2(LB_, LPPC_) CGBN_DECL_FX(LB_, LPPC_, 2)
 #define CGBN_DECL_B2(LB_, LPPC_) CGBN_DECL_BX(LB_, LPPC_, 2)
 CGBN_FUSED_BIG_SMALL(CGBN_DECL_F2)
@@ -155,7 +161,7 @@ struct Plan {
 size_t align256(size_t v) { return (v + 255) & ~(size_t)255; }
 
 void make_fused_plan(const Tuning& T, int N, int C, long long HW, int K, int layout, int eb, int words, int lds_words,
-                     int lds_words_big, int lds_words_big_small, FusedPlan* f)
+                     int lds_words_big, int lds_words_big_small, bool forward, FusedPlan* f)
 {
     std::memset(f, 0, sizeof(*f));
     if (K > kFusedMaxShards) return;
@@ -238,6 +244,30 @@ void make_fused_plan(const Tuning& T, int N, int C, long long HW, int K, int lay
                 f->rps = ips;
             }
             break;
+        }
+    }
+    // Three or four whole planes per workgroup in workgroup-wide slots, where the layout chosen above is one of the
+    // large-plane ones (a tile or two planes per workgroup) and leaves the unit markedly emptier (measured, 64 x 256
+    // planes of 100 x 100 floats forward 298 -> 284 us; 128 x 512 planes of 100 x 100 bf16 backward 904 -> 846 us)
+    if (f->LPPC <= 0 && LB == 16 && T.big_lds && K <= kFusedMaxShardsBig && N <= kFusedMaxRowsBig && N >= 2 && (long long)C * HW * eb <= 0xffffffffLL) {
+        const long long slot_bytes = (long long)kThreads * LB;
+        const long long unit_slots = R + lds_words_big / W;                      // of the variant with more unit data in LDS
+        const long long plane_bytes = HW * eb, plane_slots = (plane_bytes + slot_bytes - 1) / slot_bytes;
+        int best = 0;
+        auto consider = [&](int n) { if (unit_slots / n >= plane_slots && n <= N && n > best) best = n; };
+#define CGBN_CONSIDER(LB_, LPPC_) consider(-(LPPC_));
+        if (forward) { CGBN_FUSED_WGP_FORWARD(CGBN_CONSIDER) } else { CGBN_FUSED_WGP_BACKWARD(CGBN_CONSIDER) }
+#undef CGBN_CONSIDER
+        // planes a unit holds now
+        const double now = f->LPPC == -2 ? 2.0 : 1.0 / (double)(f->tp > 0 ? f->tp : 1);
+        if (best > 0 && (double)best >= 1.25 * now && (double)best * (double)plane_bytes >= 0.6 * (double)(unit_slots * slot_bytes)) {
+            f->LPPC = -best;
+            f->big = 1;
+            f->tp = 1;
+            f->U = (N + best - 1) / best;
+            f->IPU = best;
+            f->rows = N;
+            f->rps = ips;
         }
     }
     if (f->rows > kFusedMaxRows) return;
@@ -385,8 +415,8 @@ cgbn_status make_plan(const Tuning& T, int N, int C, int H, int W, int layout, i
     int G = 1;
     while (G < kWave && G < p->rps) G <<= 1;
     p->G = G;
-    make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, kFusedLdsWordsBigSmall, &p->ff);
-    make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, kFusedLdsWordsBigSmall / 2, &p->fb);
+    make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords, kFusedLdsWords, kFusedLdsWordsBig, kFusedLdsWordsBigSmall, true, &p->ff);
+    make_fused_plan(T, N, C, HW, K, layout, p->eb, kFusedWords / 2, kFusedLdsWords / 2, kFusedLdsWordsBig / 2, kFusedLdsWordsBigSmall / 2, false, &p->fb);
     // Tiny planes that would fill less than half of the register slots a single-launch variant reserves for a plane
     // run faster through the multi-sweep kernels for tiny planes (measured, 256 images, fwd / bwd us: fp32 7x7 x 1024
     // channels 46 / 58 against 132 / 105; bf16 14x14 x 1024 channels, forward, 85 against 126.  Half full, fp32
@@ -658,6 +688,17 @@ cgbn_status launch_fused_t(const Tuning& knobs, const FusedPlan& f, FusedArgs& A
         if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, 16, -2, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes);
         else return launch_fused_kernel(nchw_fused_backward<T, 16, -2, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes);
     }
+#define CGBN_FUSED_CASE1(LB_, LPPC_)                                                                         \
+    if (f.big == 1 && f.LB == LB_ && f.LPPC == LPPC_) {                                                      \
+        if constexpr (FWD) return launch_fused_kernel(nchw_fused_forward<T, LB_, LPPC_, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes); \
+        else return launch_fused_kernel(nchw_fused_backward<T, LB_, LPPC_, ACT, 1>, knobs, f, A, sync_words, st, taken, moved_bytes); \
+    }
+    if constexpr (FWD) {
+        CGBN_FUSED_WGP_FORWARD(CGBN_FUSED_CASE1)
+    } else {
+        CGBN_FUSED_WGP_BACKWARD(CGBN_FUSED_CASE1)
+    }
+#undef CGBN_FUSED_CASE1
 #define CGBN_FUSED_CASE2(LB_, LPPC_)                                                                         \
     if constexpr (fused_built<T, FWD, ACT>(LB_, LPPC_))                                                      \
     if (f.big == 2 && f.LB == LB_ && f.LPPC == LPPC_) {                                                      \

@@ -11,6 +11,9 @@ CGBN_FUSED_COMMON(CGBN_X)
 CGBN_FUSED_FORWARD_ONLY(CGBN_X)
 template __global__ void nchw_fused_forward<CGBN_INST_T, 16, 0, CGBN_INST_ACT, 1>(FusedArgs);      // big-LDS variants
 template __global__ void nchw_fused_forward<CGBN_INST_T, 16, -2, CGBN_INST_ACT, 1>(FusedArgs);
+#define CGBN_X1(LB_, LPPC_) template __global__ void nchw_fused_forward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT, 1>(FusedArgs);
+CGBN_FUSED_WGP_FORWARD(CGBN_X1)
+#undef CGBN_X1
 #define CGBN_X2(LB_, LPPC_) template __global__ void nchw_fused_forward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT, 2>(FusedArgs);
 CGBN_FUSED_BIG_SMALL(CGBN_X2)
 #else
@@ -18,6 +21,9 @@ CGBN_FUSED_BIG_SMALL(CGBN_X2)
 #define CGBN_X2(LB_, LPPC_) template __global__ void nchw_fused_backward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT, 2>(FusedArgs);
 template __global__ void nchw_fused_backward<CGBN_INST_T, 16, 0, CGBN_INST_ACT, 1>(FusedArgs);     // big-LDS variants
 template __global__ void nchw_fused_backward<CGBN_INST_T, 16, -2, CGBN_INST_ACT, 1>(FusedArgs);
+#define CGBN_X1(LB_, LPPC_) template __global__ void nchw_fused_backward<CGBN_INST_T, LB_, LPPC_, CGBN_INST_ACT, 1>(FusedArgs);
+CGBN_FUSED_WGP_BACKWARD(CGBN_X1)
+#undef CGBN_X1
 #if CGBN_INST_F32 && CGBN_INST_ACT == 1
 // (the float ReLU backward with 4-byte accesses: see CGBN_FUSED_RELU_BWD_F32_NARROW)
 CGBN_FUSED_COMMON_WIDE(CGBN_X)

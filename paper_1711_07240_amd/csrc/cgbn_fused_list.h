@@ -19,6 +19,17 @@
 #define CGBN_FUSED_BACKWARD_ONLY_NARROW(X) X(4, 4) X(4, 5) X(4, 6)
 #define CGBN_FUSED_BACKWARD_ONLY(X) CGBN_FUSED_BACKWARD_ONLY_WIDE(X) CGBN_FUSED_BACKWARD_ONLY_NARROW(X)
 
+// Slots per plane -N: N whole planes of one channel (consecutive images) per workgroup, in workgroup-wide slots of
+// 256 lanes x 16 bytes, a row each.  -2 is built for both LDS splits (it is in the common list); 3 and 4 planes per
+// workgroup only for the split that keeps more unit data in LDS (few rows and shards to stage).  They serve planes
+// too long for a wavefront and much shorter than half a tile (forward 38-56 KiB, backward 19-28 KiB per tensor),
+// which two to a workgroup fill 45-65 % of what it can hold.  (Measured and not built: 5 to 8 planes per workgroup
+// in place of one plane per wavefront for planes of 9-32 KiB.  The units are fuller, 75-90 % against 40-56 %, and
+// no faster: fp32 50x84 planes forward 244 -> 251 us, fp32 50x50 backward 439 -> 462 us; the two barriers per plane
+// and pass cost what the fuller units gain.)
+#define CGBN_FUSED_WGP_FORWARD(X) X(16, -3) X(16, -4)
+#define CGBN_FUSED_WGP_BACKWARD(X) X(16, -3) X(16, -4)
+
 // Small planes with few rows and shards to stage (BIG == 2): further whole planes per wavefront in LDS.
 // Only slot counts for which at least one plane fits the LDS share of either direction.
 #define CGBN_FUSED_BIG_SMALL_WIDE(X) X(8, 4) X(8, 5) X(8, 6) X(8, 8) X(8, 10) X(16, 2) X(16, 3) X(16, 4) X(16, 5)

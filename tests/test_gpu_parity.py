@@ -123,6 +123,18 @@ SMALL = [
     ("nhwc-f32-c256-long-shard", dict(N=2, C=256, H=60, W=70, K=1, layout="NHWC", dtype="f32")),
     ("nhwc-bf16-c128", dict(N=4, C=128, H=33, W=35, K=2, layout="NHWC", dtype="bf16")),
     ("nhwc-bf16-c64-long-shard", dict(N=2, C=64, H=50, W=41, K=2, layout="NHWC", dtype="bf16")),
+    # three or four whole planes per workgroup in workgroup-wide slots, image counts that are not multiples of them,
+    # planes that end inside a slot; and planes of 10-31 KB that stay one or two to a wavefront
+    ("nchw-f32-plane17408", dict(N=10, C=3, H=68, W=64, K=5, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane21888-3-per-group-bwd", dict(N=9, C=3, H=72, W=76, K=3, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane26240-3-per-group-bwd", dict(N=8, C=2, H=80, W=82, K=2, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane30976", dict(N=7, C=2, H=88, W=88, K=7, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane40000-4-per-group-fwd", dict(N=6, C=3, H=100, W=100, K=3, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane48000-3-per-group-fwd", dict(N=5, C=2, H=120, W=100, K=5, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane10000", dict(N=16, C=3, H=50, W=50, K=4, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane14400", dict(N=12, C=2, H=60, W=60, K=4, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane20000-4-per-group-bwd", dict(N=9, C=2, H=100, W=100, K=3, layout="NCHW", dtype="bf16")),
+    ("nchw-bf16-plane10368", dict(N=15, C=2, H=72, W=72, K=5, layout="NCHW", dtype="bf16")),
     # tiny NCHW planes, C a multiple of 8: a run of planes of consecutive channels per workgroup (multi-sweep path);
     # odd element counts in bf16, planes shorter than a 16-byte vector, a ragged last channel group, one pixel
     ("nchw-bf16-tiny-7x7", dict(N=8, C=64, H=7, W=7, K=4, layout="NCHW", dtype="bf16")),

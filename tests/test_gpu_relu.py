@@ -47,6 +47,9 @@ CASES = [
     ("nchw-bf16-wave", dict(N=4, C=6, H=33, W=35, K=2, layout="NCHW", dtype="bf16")),
     ("nchw-bf16-block", dict(N=2, C=2, H=160, W=161, K=2, layout="NCHW", dtype="bf16")),
     ("nchw-bf16-plane2600", dict(N=6, C=4, H=50, W=52, K=3, layout="NCHW", dtype="bf16")),
+    ("nchw-f32-plane17408", dict(N=10, C=3, H=68, W=64, K=5, layout="NCHW", dtype="f32")),
+    ("nchw-f32-plane21888-3-per-group-bwd", dict(N=9, C=3, H=72, W=76, K=3, layout="NCHW", dtype="f32")),
+    ("nchw-bf16-plane10368", dict(N=15, C=2, H=72, W=72, K=5, layout="NCHW", dtype="bf16")),
     ("nchw-bf16-tiny-7x7", dict(N=8, C=64, H=7, W=7, K=4, layout="NCHW", dtype="bf16")),
     ("nchw-f32-tiny-3x3", dict(N=6, C=24, H=3, W=3, K=3, layout="NCHW", dtype="f32")),
     ("nchw-bf16-tiny-13x21-odd", dict(N=4, C=24, H=13, W=21, K=2, layout="NCHW", dtype="bf16")),

@@ -32,7 +32,8 @@ def _built():
             out |= pairs(sub)
         return out
 
-    return {name: pairs(name) for name in ("COMMON", "FORWARD_ONLY", "BACKWARD_ONLY", "BIG_SMALL", "RELU_BWD_F32_NARROW")}
+    return {name: pairs(name) for name in ("COMMON", "FORWARD_ONLY", "BACKWARD_ONLY", "BIG_SMALL", "RELU_BWD_F32_NARROW",
+                                           "WGP_FORWARD", "WGP_BACKWARD")}
 
 
 BUILT = _built()
@@ -141,15 +142,19 @@ def _check_fused(shape, direction):
         assert (LB, LPPC) in lists, "no such kernel is built"
         if big == 2:
             assert N <= BIG_ROWS and K <= BIG_SHARDS_SMALL
-    elif LPPC == -2:                                 # two planes of at most half a tile per workgroup
-        assert LB == 16 and big in (0, 1) and g("tp") == 1 and N >= 2
-        spw = (R + ldsw // Wd) // 2
-        assert _ceil(HW * eb, THREADS * LB) <= spw, "each plane must fit half the workgroup's slots"
-        assert U == _ceil(N, 2) and rows == N and g("rps") == ips
+    elif LPPC < 0:                                   # several whole planes per workgroup, in workgroup-wide slots
+        ppu = -LPPC
+        assert LB == 16 and big in (0, 1) and g("tp") == 1 and N >= ppu >= 2
+        spw = (R + ldsw // Wd) // ppu
+        assert _ceil(HW * eb, THREADS * LB) <= spw, "each plane must fit its share of the workgroup's slots"
+        assert U == _ceil(N, ppu) and rows == N and g("rps") == ips
         assert C * HW * eb <= 2 ** 32 - 1
         if big == 1:
             assert rows <= BIG_ROWS and K <= BIG_SHARDS_LARGE
-        assert (16, -2) in BUILT["COMMON"]
+        if ppu == 2:
+            assert (16, -2) in BUILT["COMMON"]
+        else:
+            assert big == 1 and (16, LPPC) in BUILT["WGP_FORWARD" if direction == "fwd" else "WGP_BACKWARD"]
     else:                                            # large planes cut into equal tiles
         assert LB in (8, 16) and big in (0, 1)
         tp, TL = g("tp"), g("TL")

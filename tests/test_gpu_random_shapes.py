@@ -19,6 +19,30 @@ pytestmark = pytest.mark.gpu
 BASE = synth.WORKLOADS["cfg1"]
 
 
+def _draw_tiny(count, seed):
+    """NCHW shapes for the kernels that take runs of tiny planes (C a multiple of 8, planes up to 2 KiB), and
+    planes of 19-56 KB with enough images for three or four planes per workgroup."""
+    r = np.random.default_rng(seed)
+    shapes = []
+    while len(shapes) < count:
+        dtype = "f32" if r.random() < 0.5 else "bf16"
+        K = int(r.choice([1, 2, 3, 4]))
+        if r.random() < 0.7:
+            N = K * int(r.integers(1, 5))
+            C = int(r.choice([8, 16, 24, 40, 64, 136, 264]))
+            H, W = int(r.integers(1, 25)), int(r.integers(1, 25))
+            if H * W * (4 if dtype == "f32" else 2) > 2048:
+                continue
+        else:
+            N = K * int(r.integers(2, 5))
+            C = int(r.integers(1, 4))
+            H, W = int(r.integers(60, 130)), int(r.integers(80, 130))
+        if N * C * H * W > 1_500_000:
+            continue
+        shapes.append(dict(N=N, C=C, H=H, W=W, K=K, layout="NCHW", dtype=dtype))
+    return shapes
+
+
 def _draw_shapes(count, seed, wide=False):
     r = np.random.default_rng(seed)
     shapes = []
@@ -47,7 +71,7 @@ def _draw_shapes(count, seed, wide=False):
     return shapes
 
 
-SHAPES = _draw_shapes(48, 20240607) + _draw_shapes(72, 20240608, wide=True)
+SHAPES = _draw_shapes(48, 20240607) + _draw_shapes(72, 20240608, wide=True) + _draw_tiny(40, 20240609)
 
 
 @pytest.mark.parametrize("fused", [1, 0], ids=["fused", "sweeps"])

@@ -555,7 +555,11 @@ cgbn_status launch_combine(int mode, const Plan& p, char* ws, float* out0, float
     else { A.row_mod = p.pps; A.row_full = p.PL; A.row_total = p.spix; }
     dim3 block(kThreads);
     if (p.layout == CGBN_NHWC) {       // a row's channels side by side: 16 channels per workgroup
-        dim3 grid((unsigned)((p.C + 15) / 16));
+        constexpr int RL = kThreads / kCombineChannels;
+        int G = 1;                     // row lanes per shard: as many as the shard count and a shard's rows allow
+        while (2 * G * p.K <= RL && 2 * G <= p.rps) G <<= 1;
+        A.G = G;
+        dim3 grid((unsigned)((p.C + kCombineChannels - 1) / kCombineChannels));
         switch (mode) {
         case CM_MEAN:   hipLaunchKernelGGL((combine_rows_cl<CM_MEAN>), grid, block, 0, st, A); break;
         case CM_INVSTD: hipLaunchKernelGGL((combine_rows_cl<CM_INVSTD>), grid, block, 0, st, A); break;

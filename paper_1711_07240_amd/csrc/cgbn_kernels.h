@@ -1146,19 +1146,25 @@ __global__ __launch_bounds__(kThreads) void combine_rows(CombineArgs A)
     }
 }
 
+constexpr int kCombineChannels = 16;
 // The same for channels-last row partials ([rows][C]: a row's channels side by side).  There one wavefront per
-// channel would fetch every row from a different cache line; here a workgroup takes 16 neighbouring channels and
-// its 256 threads are 16 channels x 16 "row lanes".  Row lane j adds, for the shards j, j + 16, ... in turn, the
-// rows of the shard in order (the device sum of Algorithm 1, stored to the shard-sum arrays if wanted) and keeps
-// the running total of its shards; the 16 lane totals of a channel are then added in lane order (the reduce step).
-// Double precision, fixed order.  CM_MOMENTS: summaries merged pairwise instead of sums added, in the same order.
+// channel would fetch every row from a different cache line; here a workgroup takes CL = 16 neighbouring channels and
+// its 256 threads are CL channels x RL = 16 "row lanes".  A.G row lanes (a power of two) share one shard: each
+// adds every G-th row of the shard in order, the G partial sums are added in lane order (the device sum of
+// Algorithm 1, stored to the shard-sum arrays if wanted), and the group's first lane keeps the running total of the
+// shards the group takes in turn (k, k + RL / G, ...); the totals of a channel are then added in lane order (the
+// reduce step).  Double precision, fixed order.  CM_MOMENTS: summaries merged pairwise instead of sums added, in
+// the same order.  The host picks G as large as the shard count and the rows per shard allow, so that a lane walks
+// few rows one after the other (8 or 4 channels per workgroup, for more workgroups, measured the same).
 template <int MODE>
 __global__ __launch_bounds__(kThreads) void combine_rows_cl(CombineArgs A)
 {
     constexpr int Q = (MODE == CM_BWD || MODE == CM_SHARDS2 || MODE == CM_MOMENTS) ? 2 : 1;
-    __shared__ double tot[3][16][16];           // [what][row lane][channel]
-    const int t = threadIdx.x, cl = t & 15, rl = t >> 4;
-    const int c = blockIdx.x * 16 + cl;
+    constexpr int CL = kCombineChannels, RL = kThreads / CL;   // channels, row lanes
+    __shared__ double tot[3][RL][CL];           // [what][row lane][channel]
+    const int t = threadIdx.x, cl = t % CL, rl = t / CL;
+    const int G = A.G, gl = rl & (G - 1), gi = rl / G, spp = RL / G;
+    const int c = blockIdx.x * CL + cl;
     if (A.clear_word && blockIdx.x == 0 && t == 0) *A.clear_word = 0u;
     const bool live = c < A.C;
     const double pivot = live ? pivot_of(A, c) : 0.0;
@@ -1168,27 +1174,29 @@ __global__ __launch_bounds__(kThreads) void combine_rows_cl(CombineArgs A)
     const double n_last = (double)(A.row_total - (A.row_mod - 1) * A.row_full);
     const double r_full = MODE == CM_MOMENTS ? rcp_count((double)A.row_full) : 0.0;
     const double r_last = MODE == CM_MOMENTS ? rcp_count(n_last) : 0.0;
-    if (live) {
-        const float* p0 = A.part0 + c;
-        const float* p1 = A.part1 + c;
-        for (int k = rl; k < A.K; k += 16) {
-            double a0 = 0.0, a1 = 0.0;
-            Moments sk = {0.0, 0.0, 0.0};
-            constexpr int B = 8;                 // rows fetched together
-            for (int r0 = 0; r0 < A.rps; r0 += B) {
+    const float* p0 = A.part0 + (live ? c : 0);
+    const float* p1 = A.part1 + (live ? c : 0);
+    for (int k0 = 0; k0 < A.K; k0 += spp) {      // the same trip count for every thread: barriers inside
+        const int k = k0 + gi;
+        const bool work = live && k < A.K;
+        double a0 = 0.0, a1 = 0.0;
+        Moments sk = {0.0, 0.0, 0.0};
+        constexpr int B = 8;                     // rows fetched together
+        if (work)
+            for (int r0 = gl; r0 < A.rps; r0 += B * G) {
                 float v0[B], v1[B];
 #pragma unroll
                 for (int u = 0; u < B; ++u) {
-                    const bool have = r0 + u < A.rps;
-                    const size_t o = have ? ((size_t)k * A.rps + r0 + u) * (size_t)A.C : 0;
+                    const bool have = r0 + u * G < A.rps;
+                    const size_t o = have ? ((size_t)k * A.rps + r0 + u * G) * (size_t)A.C : 0;
                     v0[u] = p0[o];
                     v1[u] = Q == 2 ? p1[o] : 0.f;
                 }
 #pragma unroll
                 for (int u = 0; u < B; ++u) {
-                    if (r0 + u < A.rps) {
+                    if (r0 + u * G < A.rps) {
                         if (MODE == CM_MOMENTS) {
-                            const long long row = (long long)k * A.rps + r0 + u;
+                            const long long row = (long long)k * A.rps + r0 + u * G;
                             const bool last = row % A.row_mod == A.row_mod - 1;
                             Moments m;
                             m.n = last ? n_last : (double)A.row_full;
@@ -1202,6 +1210,29 @@ __global__ __launch_bounds__(kThreads) void combine_rows_cl(CombineArgs A)
                     }
                 }
             }
+        if (G > 1) {                             // the group's partial results, added by its first lane in lane order
+            if (MODE == CM_MOMENTS) {
+                tot[0][rl][cl] = sk.n;
+                tot[1][rl][cl] = sk.mean;
+                tot[2][rl][cl] = sk.m2;
+            } else {
+                tot[0][rl][cl] = a0;
+                tot[1][rl][cl] = a1;
+            }
+            __syncthreads();
+            if (gl == 0)
+                for (int j = 1; j < G; ++j) {
+                    if (MODE == CM_MOMENTS) {
+                        Moments o = {tot[0][rl + j][cl], tot[1][rl + j][cl], tot[2][rl + j][cl]};
+                        sk = merge_moments(sk, o);
+                    } else {
+                        a0 += tot[0][rl + j][cl];
+                        a1 += tot[1][rl + j][cl];
+                    }
+                }
+            __syncthreads();
+        }
+        if (work && gl == 0) {
             if (MODE == CM_MOMENTS) {
                 mine = merge_moments(mine, sk);
             } else {
@@ -1224,7 +1255,7 @@ __global__ __launch_bounds__(kThreads) void combine_rows_cl(CombineArgs A)
     if (rl != 0 || !live) return;
     if (MODE == CM_MOMENTS) {
         Moments m = {tot[0][0][cl], tot[1][0][cl], tot[2][0][cl]};
-        for (int j = 1; j < 16; ++j) {
+        for (int j = G; j < RL; j += G) {
             Moments o = {tot[0][j][cl], tot[1][j][cl], tot[2][j][cl]};
             m = merge_moments(m, o);
         }
@@ -1238,7 +1269,7 @@ __global__ __launch_bounds__(kThreads) void combine_rows_cl(CombineArgs A)
         return;
     }
     double s0 = 0.0, s1 = 0.0;
-    for (int j = 0; j < 16; ++j) {
+    for (int j = 0; j < RL; j += G) {
         s0 += tot[0][j][cl];
         s1 += tot[1][j][cl];
     }

@@ -652,6 +652,13 @@ struct Slots {
     }
     // image of slot s in wavefront w (small planes)
     static __device__ __forceinline__ int image(const UnitGeom& g, int s, int w) { return g.n0 + w + 4 * (s / SPP); }
+    // Small planes: slot s opens a plane that lies beyond the unit's images, and so do all later slots (a
+    // wavefront's planes are in ascending image order): the slot loops end there instead of testing every
+    // remaining slot, which is most of a pass's instructions when a channel has fewer planes than a unit holds.
+    static __device__ __forceinline__ bool beyond(const UnitGeom& g, int s, int w)
+    {
+        return SMALL && (s % SPP) == 0 && image(g, s, w) >= g.n1;
+    }
     // is any lane of slot s in use (uniform)
     static __device__ __forceinline__ bool in_use(const FusedArgs& A, const UnitGeom& g, int s, int w)
     {
@@ -746,6 +753,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             const unsigned loff = SL::lane_offset(t);
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
+                if (SL::beyond(g, s, w)) break;
                 if (SL::in_use(A, g, s, w)) {
                     // lanes past the end re-read the slot's first bytes; they are masked later
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
@@ -946,6 +954,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_forward(FusedArgs A)
             }
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
+                if (SL::beyond(g, s, w)) break;
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t o[W], wv[W];
                     if (s < RS) {
@@ -1035,6 +1044,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
             const unsigned loff = SL::lane_offset(t);
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
+                if (SL::beyond(g, s, w)) break;
                 if (SL::in_use(A, g, s, w)) {
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
                     size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
@@ -1050,6 +1060,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
             wait_vector_memory();
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
+                if (SL::beyond(g, s, w)) break;
                 if (SL::in_use(A, g, s, w)) {
                     if (s < RS) {
 #pragma unroll
@@ -1068,6 +1079,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
             // (a wavefront's LDS entries are its own: no barrier is needed before x lands on y's slots)
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
+                if (SL::beyond(g, s, w)) break;
                 if (SL::in_use(A, g, s, w)) {
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
                     size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
@@ -1080,6 +1092,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
             const unsigned loff = SL::lane_offset(t);
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
+                if (SL::beyond(g, s, w)) break;
                 if (SL::in_use(A, g, s, w)) {
                     unsigned lo = SL::lane_ok(g, s, loff) ? loff : 0u;
                     size_t o = SL::plane_base(A, s, w) + SL::slot_offset(s) + lo;
@@ -1101,6 +1114,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
             float a[2] = {0.f, 0.f}, b[2] = {0.f, 0.f};
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
+                if (SL::beyond(g, s, w)) break;
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t wx[W], wg[W];
                     if (s < RS) {
@@ -1202,6 +1216,7 @@ __global__ __launch_bounds__(kThreads, 3) void nchw_fused_backward(FusedArgs A)
             const float k2 = gsc * istd * c2, k0 = k2 * mulo - gsc * c1, nk2 = -k2;
 #pragma unroll
             for (int s = 0; s < RT; ++s) {
+                if (SL::beyond(g, s, w)) break;
                 if (SL::in_use(A, g, s, w) && SL::lane_ok(g, s, loff)) {
                     uint32_t o[W];
                     uint32_t wx[W], wg[W];

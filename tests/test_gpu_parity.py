@@ -398,6 +398,36 @@ def test_limits_of_the_staging_areas(name, kw, fused, path):
         assert L.cgbn_get_tuning("last_forward_fused") == fwd and L.cgbn_get_tuning("last_backward_fused") == bwd
 
 
+CL_COMBINE = [
+    # (name, shape, rows per shard wanted): channels-last row partials, many rows per shard (4 KiB pieces), shard counts
+    # that give 4, 2 and 1 row lanes per shard in the combine step, and more shards than row lanes (two passes)
+    ("k3-four-lanes-per-shard", dict(N=6, C=40, H=33, W=29, K=3, layout="NHWC", dtype="f32")),
+    ("k5-two-lanes-per-shard", dict(N=10, C=24, H=21, W=23, K=5, layout="NHWC", dtype="bf16")),
+    ("k8-two-lanes-odd-rows", dict(N=8, C=16, H=71, W=53, K=8, layout="NHWC", dtype="f32")),
+    ("k12-one-lane-per-shard", dict(N=12, C=36, H=37, W=39, K=12, layout="NHWC", dtype="f32")),
+    ("k20-two-passes", dict(N=20, C=24, H=45, W=47, K=20, layout="NHWC", dtype="bf16")),
+    ("k1-sixteen-lanes", dict(N=2, C=72, H=41, W=37, K=1, layout="NHWC", dtype="f32")),
+]
+
+
+@pytest.mark.parametrize("name,kw", CL_COMBINE, ids=[c[0] for c in CL_COMBINE])
+def test_channels_last_combine_lane_groups(name, kw, path):
+    """The combine step of the channels-last kernels deals a shard's rows to 16 / K row lanes (a power of two)
+    and joins their sums in lane order: every lane count, ragged rows per lane, both statistics variants (the
+    `path` fixture's two multi-sweep settings)."""
+    if path:
+        pytest.skip("channels-last shapes take the multi-sweep kernels either way")
+    wl = BASE.scaled(name=name, **kw)
+    old = L.cgbn_get_tuning("piece_bytes")
+    try:
+        L.cgbn_set_tuning("piece_bytes", 4096)
+        rps = L.cgbn_plan_get(wl.N, wl.C, wl.H, wl.W, wl.layout, wl.dtype, wl.K, "rps")
+        assert rps >= 3, rps                      # several rows per row lane, or the case tests nothing
+        run_case(wl, f"{name} rps={rps}")
+    finally:
+        L.cgbn_set_tuning("piece_bytes", old)
+
+
 FEW_GROUPS = [
     # (shape, workgroups): large planes, one tile per plane -> 8 units per channel
     ("large-planes-8-units", dict(N=8, C=12, H=96, W=128, K=4, layout="NCHW", dtype="f32"), (8, 9, 13)),
